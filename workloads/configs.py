@@ -1,0 +1,291 @@
+"""The five synthetic workloads: shapes, hyper-parameter values and seeded input streams.
+
+Nothing here computes any quantity of the method: the functions draw random
+numbers and shape them into gradients, probe pairs and initial parameters.
+Both the CPU oracle and the HIP path are fed the arrays produced here.
+
+Notation ``N(0, x)``: ``x`` is the variance.
+
+Precision-code convention used for dtypes throughout: 0 = FP16, 1 = BF16,
+2 = FP32 (the order in which the paper's precision rule, Sec. 3.1, lists them).
+"""
+
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+import torch
+
+from . import shapes as _shapes
+
+MASTER_SEED = 20250816
+
+FP16, BF16, FP32 = 0, 1, 2
+TORCH_DTYPE = {FP16: torch.float16, BF16: torch.bfloat16, FP32: torch.float32}
+
+WORKLOAD_NAMES = ("tiny_mlp", "resnet18", "efficientnet_b0", "large_streaming", "mixed_state")
+
+_KIND = {"grad": 1, "z": 2, "hz": 3, "param": 4, "layer": 5, "hess": 6, "inject": 7, "zero": 8}
+
+
+def _mix(*vals: int) -> int:
+    """Counter-style 64-bit integer hash of a tuple of integers (splitmix64 finaliser)."""
+    x = 0x9E3779B97F4A7C15
+    for v in vals:
+        x = (x ^ (int(v) & 0xFFFFFFFFFFFFFFFF)) & 0xFFFFFFFFFFFFFFFF
+        x = (x + 0x9E3779B97F4A7C15) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 30
+        x = (x * 0xBF58476D1CE4E5B9) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 27
+        x = (x * 0x94D049BB133111EB) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 31
+    return x
+
+
+def _gen(device, *vals: int) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(_mix(*vals) & 0x7FFFFFFFFFFFFFFF)
+    return g
+
+
+_DEFAULT_HYPER = dict(
+    beta_var=0.9,
+    beta_curv=0.9,
+    tau_low=1e-5,
+    tau_high=3e-5,
+    tau_curv=1.0,
+    alpha=0.1,
+    sparsity_ppm=900000,
+    momentum=0.9,
+    weight_decay=5e-4,
+    ctrl_interval=1,
+    scale_backoff=0.5,
+    scale_growth=2.0,
+    growth_interval=2000,
+    rho_low=0.70,
+    rho_high=0.90,
+    delta_up=16,
+    delta_down=16,
+    b_min=16,
+    b_max=4096,
+    # per-step scalars the caller passes
+    lr=0.1,
+    loss_scale=1.0,
+    batch_size=96,
+)
+
+
+@dataclass
+class Workload:
+    name: str
+    index: int
+    tensors: List[Tuple[str, Tuple[int, ...]]]
+    hyper: Dict[str, float]
+    steps: int
+    grad_dtype: int = FP32
+    param_dtypes: Optional[List[int]] = None  # initial storage dtype per tensor
+    grad_kind: str = "normal"  # "normal" | "student_t"
+    probe_kind: str = "diag_noise"  # "diag_noise" | "block_hessian"
+    inject_every: int = 0  # >0: non-finite gradient elements on steps t % inject_every == 0
+    seed: int = 0
+    _layer_cache: Dict[int, Dict[str, float]] = field(default_factory=dict, repr=False)
+    _hess_cache: Dict[int, object] = field(default_factory=dict, repr=False)
+
+    # ---- structure -------------------------------------------------------
+    @property
+    def n_tensors(self) -> int:
+        return len(self.tensors)
+
+    def numel(self, l: int) -> int:
+        return _shapes.numel(self.tensors[l][1])
+
+    @property
+    def total_params(self) -> int:
+        return sum(self.numel(l) for l in range(self.n_tensors))
+
+    def init_dtype(self, l: int) -> int:
+        return FP32 if self.param_dtypes is None else self.param_dtypes[l]
+
+    # ---- per-layer constants (drawn once per tensor) ------------------------
+    def layer_consts(self, l: int) -> Dict[str, float]:
+        if l in self._layer_cache:
+            return self._layer_cache[l]
+        rs = np.random.Generator(np.random.Philox(key=_mix(self.seed, _KIND["layer"], l)))
+        c: Dict[str, float] = {}
+        if self.name == "tiny_mlp":
+            c["sigma"] = (1e-2, 1e-3, 1e-2, 1e-3)[l % 4]
+        elif self.name in ("resnet18", "efficientnet_b0"):
+            c["sigma"] = float(10.0 ** rs.uniform(-4.0, -2.0))  # scale of the Student-t draw
+        elif self.name == "large_streaming":
+            c["sigma"] = math.sqrt(1e-3)
+        elif self.name == "mixed_state":
+            # variance bands that the precision rule (tau_low = 1e-6, tau_high = 1e-4) maps
+            # back to the tensor's pre-assigned storage dtype
+            band = {FP16: (1e-8, 5e-7), BF16: (2e-6, 5e-5), FP32: (2e-4, 1e-2)}[self.init_dtype(l)]
+            var = float(10.0 ** rs.uniform(math.log10(band[0]), math.log10(band[1])))
+            c["sigma"] = math.sqrt(var)
+        c["d"] = float(10.0 ** rs.uniform(-5.0, 0.0))  # curvature level of the layer
+        self._layer_cache[l] = c
+        return c
+
+    # ---- initial parameters -------------------------------------------------
+    def init_param(self, l: int, device="cpu") -> torch.Tensor:
+        """N(0, 0.01) draw, stored in the tensor's initial dtype (flat)."""
+        g = _gen(device, self.seed, _KIND["param"], l)
+        p = torch.randn(self.numel(l), generator=g, device=device, dtype=torch.float32) * 0.1
+        return p.to(TORCH_DTYPE[self.init_dtype(l)])
+
+    # ---- gradients --------------------------------------------------------------
+    def grad(self, step: int, l: int, loss_scale: float = 1.0, device="cpu") -> torch.Tensor:
+        """Stored gradient of tensor ``l`` at 1-based ``step``: true gradient times ``loss_scale``
+        in the workload's gradient dtype (flat)."""
+        n = self.numel(l)
+        sigma = self.layer_consts(l)["sigma"]
+        g = _gen(device, self.seed, _KIND["grad"], step, l)
+        if self.grad_kind == "student_t":
+            # t(3) = N / sqrt(chi2_3 / 3), then 10 % exact zeros
+            num = torch.randn(n, generator=g, device=device, dtype=torch.float32)
+            den = torch.randn(3, n, generator=g, device=device, dtype=torch.float32)
+            x = num / torch.sqrt((den * den).sum(0) / 3.0)
+            keep = torch.rand(n, generator=g, device=device) >= 0.10
+            x = x * sigma * keep
+        else:
+            x = torch.randn(n, generator=g, device=device, dtype=torch.float32) * sigma
+        x = (x * float(loss_scale)).to(TORCH_DTYPE[self.grad_dtype])
+        if self.inject_every and step % self.inject_every == 0:
+            victim = _mix(self.seed, _KIND["inject"], step) % self.n_tensors
+            if victim == l:
+                count = 1 + _mix(self.seed, _KIND["inject"], step, 1) % 3
+                specials = (float("inf"), float("-inf"), float("nan"))
+                for j in range(count):
+                    pos = _mix(self.seed, _KIND["inject"], step, 2, j) % n
+                    x[pos] = specials[(step // self.inject_every + j) % 3]
+        return x
+
+    def injected_tensor(self, step: int) -> Optional[int]:
+        if self.inject_every and step % self.inject_every == 0:
+            return _mix(self.seed, _KIND["inject"], step) % self.n_tensors
+        return None
+
+    # ---- probe pairs ----------------------------------------------------------------
+    def probe(self, step: int, l: int, loss_scale: float = 1.0, device="cpu"):
+        """Rademacher ``z`` and ``Hz`` (times ``loss_scale``), both fp32 and flat."""
+        n = self.numel(l)
+        g = _gen(device, self.seed, _KIND["z"], step, l)
+        z = (torch.randint(0, 2, (n,), generator=g, device=device, dtype=torch.int32) * 2 - 1).to(torch.float32)
+        if self.probe_kind == "block_hessian":
+            hz = self._block_hessian_times(l, z.cpu().numpy().astype(np.float64))
+            hz = torch.from_numpy((hz * float(loss_scale)).astype(np.float32)).to(device)
+        else:
+            d = self.layer_consts(l)["d"]
+            gn = _gen(device, self.seed, _KIND["hz"], step, l)
+            noise = torch.randn(n, generator=gn, device=device, dtype=torch.float32) * math.sqrt(0.1 * d)
+            hz = (z * d + noise) * float(loss_scale)
+        return z, hz
+
+    # ---- block-diagonal quadratic (tiny_mlp) -------------------------------------------
+    BLOCK = 32
+
+    def block_hessian(self, l: int):
+        """Block-diagonal Hessian of the synthetic quadratic for tensor ``l``.
+
+        Returns ``(nonzero, blocks)``: ``nonzero[b]`` says whether block ``b`` is non-zero and
+        ``blocks[b]`` is its dense symmetric positive-definite matrix ``Q diag(lam) Q^T`` with
+        ``lam ~ U[1e-3, 10]`` (float64; the last block may be smaller than 32).
+        """
+        if l in self._hess_cache:
+            return self._hess_cache[l]
+        n = self.numel(l)
+        nb = (n + self.BLOCK - 1) // self.BLOCK
+        rs = np.random.Generator(np.random.Philox(key=_mix(self.seed, _KIND["hess"], l)))
+        nonzero = rs.uniform(size=nb) < 0.10
+        if not nonzero.any():
+            nonzero[int(rs.integers(nb))] = True
+        blocks = {}
+        for b in np.nonzero(nonzero)[0]:
+            sz = min(self.BLOCK, n - b * self.BLOCK)
+            q, _ = np.linalg.qr(rs.standard_normal((sz, sz)))
+            lam = rs.uniform(1e-3, 10.0, size=sz)
+            hb = (q * lam) @ q.T
+            blocks[int(b)] = 0.5 * (hb + hb.T)
+        self._hess_cache[l] = (nonzero, blocks)
+        return self._hess_cache[l]
+
+    def hessian_diagonal(self, l: int) -> np.ndarray:
+        n = self.numel(l)
+        _, blocks = self.block_hessian(l)
+        d = np.zeros(n)
+        for b, hb in blocks.items():
+            d[b * self.BLOCK : b * self.BLOCK + hb.shape[0]] = np.diag(hb)
+        return d
+
+    def hessian_offdiag_sq(self, l: int) -> np.ndarray:
+        """sum_{j != i} H_ij^2 per element (the variance of one Rademacher sample z_i (Hz)_i)."""
+        n = self.numel(l)
+        _, blocks = self.block_hessian(l)
+        s = np.zeros(n)
+        for b, hb in blocks.items():
+            sq = (hb * hb).sum(1) - np.diag(hb) ** 2
+            s[b * self.BLOCK : b * self.BLOCK + hb.shape[0]] = sq
+        return s
+
+    def _block_hessian_times(self, l: int, z: np.ndarray) -> np.ndarray:
+        _, blocks = self.block_hessian(l)
+        out = np.zeros_like(z)
+        for b, hb in blocks.items():
+            lo = b * self.BLOCK
+            out[lo : lo + hb.shape[0]] = hb @ z[lo : lo + hb.shape[0]]
+        return out
+
+
+def _split_dtypes(n: int, seed: int) -> List[int]:
+    """40 % FP32 / 40 % BF16 / 20 % FP16, assigned by a seeded shuffle."""
+    n32 = int(round(0.4 * n))
+    n16b = int(round(0.4 * n))
+    kinds = [FP32] * n32 + [BF16] * n16b + [FP16] * (n - n32 - n16b)
+    rs = np.random.Generator(np.random.Philox(key=_mix(seed, 99)))
+    rs.shuffle(kinds)
+    return [int(k) for k in kinds]
+
+
+def get_workload(name: str, **scale) -> Workload:
+    """Build a workload by name.
+
+    Optional keyword arguments shrink the two large sets for element-by-element tests:
+    ``large_streaming``: ``n_tensors``, ``side``; ``mixed_state``: ``n_square``, ``n_wide``,
+    ``rows``.  ``steps`` overrides the step count of any workload.
+    """
+    if name not in WORKLOAD_NAMES:
+        raise KeyError(f"unknown workload {name!r}; choose from {WORKLOAD_NAMES}")
+    idx = WORKLOAD_NAMES.index(name)
+    seed = MASTER_SEED + idx
+    hyper = dict(_DEFAULT_HYPER)
+    steps = scale.pop("steps", None)
+    if name == "tiny_mlp":
+        hyper.update(sparsity_ppm=900000, tau_low=1e-5, tau_high=3e-5, tau_curv=6.5)
+        wl = Workload(name, idx, _shapes.tiny_mlp_shapes(), hyper, 20, probe_kind="block_hessian", seed=seed)
+    elif name == "resnet18":
+        hyper.update(sparsity_ppm=950000, tau_low=1e-6, tau_high=3e-5, tau_curv=0.1)
+        wl = Workload(name, idx, _shapes.resnet18_cifar_shapes(), hyper, 100, grad_kind="student_t", seed=seed)
+    elif name == "efficientnet_b0":
+        hyper.update(sparsity_ppm=950000, tau_low=1e-6, tau_high=3e-5, tau_curv=0.1, loss_scale=65536.0)
+        wl = Workload(name, idx, _shapes.efficientnet_b0_shapes(), hyper, 100, grad_kind="student_t", seed=seed)
+    elif name == "large_streaming":
+        hyper.update(sparsity_ppm=950000, tau_low=1e-4, tau_high=1e-2, tau_curv=0.1)
+        wl = Workload(name, idx, _shapes.large_streaming_shapes(**scale), hyper, 13, seed=seed)
+    else:
+        hyper.update(
+            sparsity_ppm=950000, tau_low=1e-6, tau_high=1e-4, tau_curv=0.5,
+            loss_scale=32768.0, growth_interval=5,
+        )
+        tensors = _shapes.mixed_state_shapes(**scale)
+        wl = Workload(
+            name, idx, tensors, hyper, 50, grad_dtype=FP16,
+            param_dtypes=_split_dtypes(len(tensors), seed), inject_every=7, seed=seed,
+        )
+    if steps is not None:
+        wl.steps = int(steps)
+    return wl

@@ -1,0 +1,186 @@
+/*
+ * triaccel.h -- C ABI of the MI355X (gfx950) Tri-Accel optimizer-step library.
+ *
+ * The library runs, for a list of parameter tensors ("layers"), the per-layer
+ * fused optimizer step of Tri-Accel (arXiv 2508.16905):
+ *
+ *   gradient statistics        Var[grad_l(t)] and the EMA v_l(t)         Sec. 3.1, first equation
+ *   precision rule             p_l(t) in {FP16, BF16, FP32}              Sec. 3.1, second equation
+ *   sparse curvature signal    diagonal Hutchinson EMA, top-k magnitude  Sec. 3.2 (and Sec. 1:
+ *                              mask, lambda_l = largest kept magnitude   "top-k Hessian or Fisher entries")
+ *   step-size scaling          eta_l = eta_0 / (1 + alpha lambda_l)      Sec. 3.2, "Step size scaling"
+ *   precision promotion        lambda_l > tau_curv -> one level up       Sec. 3.2, "Precision promotion"
+ *   memory-elastic batch rule  B(t+1) from MemUsage / MemMax             Sec. 3.3
+ *   control loop               the order of the stages                   Sec. 3.4
+ *   overflow skip, loss scale  dynamic loss scaling (prior art, Sec. 2)
+ *
+ * All pointers inside triaccel_tensor are DEVICE pointers owned by the caller
+ * (allocated e.g. by PyTorch-ROCm).  All other pointers are HOST pointers.  The
+ * library owns only its internal workspace, released by triaccel_destroy().
+ *
+ * Every device operation is enqueued on the HIP stream given to triaccel_init();
+ * triaccel_step() never synchronises.  One step may be in flight per handle.
+ *
+ * Precision codes / dtypes:  0 = FP16 (IEEE binary16), 1 = BF16, 2 = FP32 --
+ * the order of the cases in the precision rule, so "promotion" is +1.
+ *
+ * Return values: 0 on success, a negative TRIACCEL_E_* code otherwise.  Arguments
+ * are validated before anything is enqueued; a call that returns an error has
+ * changed no optimizer state.  A skipped step (non-finite gradient) is not an error.
+ */
+#ifndef TRIACCEL_H
+#define TRIACCEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TRIACCEL_FP16 0
+#define TRIACCEL_BF16 1
+#define TRIACCEL_FP32 2
+
+#define TRIACCEL_OK 0
+#define TRIACCEL_E_INVALID_ARG (-1)     /* value out of range, wrong struct_size, n <= 0 ...        */
+#define TRIACCEL_E_BAD_DTYPE (-2)       /* dtype code not in {0, 1, 2}                               */
+#define TRIACCEL_E_SHAPE_MISMATCH (-3)  /* tensor list differs from the one given to triaccel_init   */
+#define TRIACCEL_E_NULL_PTR (-4)        /* a required pointer is NULL                                */
+#define TRIACCEL_E_ALIGNMENT (-5)       /* a device pointer is not 16-byte aligned                   */
+#define TRIACCEL_E_HIP (-6)             /* a HIP runtime call failed; see triaccel_last_error()      */
+#define TRIACCEL_E_NOT_INITIALISED (-7) /* NULL / destroyed handle, or result before any step        */
+#define TRIACCEL_E_NO_MEMORY (-8)       /* host or device allocation failed                          */
+
+typedef struct triaccel_ctx *triaccel_handle;
+
+/* Hyper-parameters, fixed at init.  Symbols are the paper's where it has one. */
+typedef struct {
+  uint32_t struct_size;    /* sizeof(triaccel_config) */
+  float beta_var;          /* beta of the variance EMA (Sec. 3.1), in [0, 1)                       */
+  float beta_curv;         /* smoothing factor of the curvature EMA, in [0, 1)                     */
+  float tau_low, tau_high; /* precision thresholds (Sec. 3.1), tau_low <= tau_high                  */
+  float tau_curv;          /* promotion threshold on lambda_l (Sec. 3.2)                            */
+  float alpha;             /* step-size coefficient (Sec. 3.2), >= 0                                */
+  uint32_t sparsity_ppm;   /* curvature sparsity s in parts per million: the mask keeps the
+                              k_l = clamp(n_l - floor(n_l * s / 1e6), 1, n_l) largest |h_i|         */
+  float momentum;          /* mu of the base SGD update (Sec. 4.1 uses 0.9); 0 = no buffer          */
+  float weight_decay;      /* coupled L2 coefficient                                                */
+  int32_t ctrl_interval;   /* T_ctrl (Sec. 3.4): codes and the curvature used for eta_l are
+                              re-evaluated on applied steps t with t % T_ctrl == 0; >= 1            */
+  float scale_backoff;     /* loss-scale factor after a skipped step (e.g. 0.5)                     */
+  float scale_growth;      /* loss-scale factor after growth_interval good steps (e.g. 2)           */
+  int32_t growth_interval; /* >= 1                                                                  */
+  double rho_low, rho_high;     /* memory utilisation thresholds (Sec. 3.3)                         */
+  int32_t delta_up, delta_down; /* batch-size steps (Sec. 3.3)                                      */
+  int32_t b_min, b_max;         /* clamp of the batch size                                          */
+} triaccel_config;
+
+/* One parameter tensor.  Contiguous, flat; numel elements. */
+typedef struct {
+  void *param;       /* device; capacity 4*numel bytes.  Holds numel elements of the tensor's CURRENT
+                        precision code at the start of the buffer (the library tracks the code;
+                        param_dtype below is only read by triaccel_init)                            */
+  const void *grad;  /* device; numel elements of grad_dtype; the true gradient times loss_scale   */
+  const float *z;    /* device; Rademacher probe (+-1.0f); NULL = no curvature probe this step      */
+  const float *hz;   /* device; Hessian-vector product H z times loss_scale; NULL iff z is NULL     */
+  float *curv;       /* device; fp32[numel]; diagonal curvature EMA h (library-updated state)       */
+  float *mom;        /* device; fp32[numel]; momentum buffer m; may be NULL iff momentum == 0       */
+  uint32_t *mask;    /* device; ceil(numel/32) words; bit (i % 32) of word (i / 32) = element i kept */
+  int64_t numel;     /* 0 < numel < 2^31                                                            */
+  int32_t grad_dtype;  /* precision code of the gradient buffer                                     */
+  int32_t param_dtype; /* precision code of the parameters at init; ignored by triaccel_step        */
+} triaccel_tensor;
+
+/* Per-step scalars. */
+typedef struct {
+  uint32_t struct_size;     /* sizeof(triaccel_step_args) */
+  float lr;                 /* eta_0 of this step (the caller applies its own schedule)             */
+  float loss_scale;         /* S > 0: gradients and hz arrive multiplied by S                       */
+  int32_t batch_size;       /* B(t), input of the batch rule                                        */
+  uint64_t mem_used_bytes;  /* MemUsage(t); with mem_total_bytes == 0 the library asks the HIP      */
+  uint64_t mem_total_bytes; /* MemMax       runtime (hipMemGetInfo) for both                        */
+} triaccel_step_args;
+
+typedef struct {
+  uint32_t struct_size;    /* sizeof(triaccel_step_result), set by the caller */
+  int32_t skipped;         /* 1: a gradient held inf/NaN; no optimizer state was changed            */
+  uint64_t step_index;     /* number of triaccel_step calls so far                                  */
+  float next_loss_scale;   /* loss scale to use for the next step                                   */
+  int32_t next_batch_size; /* B(t+1), Sec. 3.3                                                      */
+} triaccel_step_result;
+
+/* Per-layer record; same layout on the device and in the host copy. */
+typedef struct {
+  int64_t numel;
+  float mean, var;      /* of the unscaled gradient at the last applied step (population variance)  */
+  float v;              /* variance EMA v_l (Sec. 3.1)                                              */
+  float theta;          /* magnitude threshold of the mask                                          */
+  uint32_t nnz;         /* popcount of the mask                                                     */
+  float lambda;         /* largest kept |h_i|                                                       */
+  float lambda_ctrl;    /* lambda latched at the last control step (used by eta and promotion)      */
+  float eta;            /* per-layer step size (Sec. 3.2)                                           */
+  int32_t code;         /* precision the parameters are stored in now                               */
+  int32_t prev_code;    /* precision before the last applied step                                   */
+  uint32_t found_inf;   /* this tensor's gradient held inf/NaN at the last step                     */
+  uint32_t curv_nonfinite; /* a probe sample was non-finite at the last probed step (element frozen) */
+} triaccel_layer_info;
+
+/* Stage timings of the last step (only filled while profiling is on). */
+#define TRIACCEL_N_STAGES 6
+typedef struct {
+  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram, 2 threshold
+                                  refinement passes, 3 mask, 4 per-layer assign, 5 update + cast   */
+} triaccel_stage_times;
+
+/*
+ * Create a handle for n tensors.  `tensors` gives shapes, dtypes and the initial pointers;
+ * curv / mom / mask contents are taken as the initial state (normally zero).  `hip_stream` is a
+ * hipStream_t (NULL = the default stream).  Allocates the workspace (chunk table, partials,
+ * histograms, candidate lists, per-layer state; a few MB plus 16 bytes per 4096 parameters).
+ */
+int triaccel_init(triaccel_handle *out, const triaccel_config *config, const triaccel_tensor *tensors,
+                  int32_t n, void *hip_stream);
+
+/*
+ * Enqueue one optimizer step (Sec. 3.4 control loop, stages 1-3; stage 4 runs on the host).
+ * `tensors` must have the n, numel and grad_dtype given at init; pointers may differ from call
+ * to call.  Asynchronous: returns once the kernels are enqueued.
+ */
+int triaccel_step(triaccel_handle h, const triaccel_tensor *tensors, int32_t n, const triaccel_step_args *args);
+
+/* Wait for the last enqueued step and return its record. */
+int triaccel_result(triaccel_handle h, triaccel_step_result *out);
+
+/* Wait for the stream and copy the n per-layer records to `out` (host). */
+int triaccel_layer_state(triaccel_handle h, triaccel_layer_info *out, int32_t n);
+
+/* Batch rule of Sec. 3.3 as a pure host function; returns B(t+1), or B unchanged if config is NULL. */
+int32_t triaccel_batch_next(const triaccel_config *config, int32_t batch_size, uint64_t mem_used_bytes,
+                            uint64_t mem_total_bytes);
+
+/* Release the workspace.  Waits for the stream first.  NULL is allowed. */
+void triaccel_destroy(triaccel_handle h);
+
+/* Static text for an error code. */
+const char *triaccel_strerror(int code);
+
+/* Text of the last HIP failure on this thread ("" if none). */
+const char *triaccel_last_error(void);
+
+/* Record HIP events between the stages of every following step (on != 0) or stop doing so. */
+int triaccel_set_profiling(triaccel_handle h, int32_t on);
+
+/* Wait for the last step and return its stage timings; needs profiling on. */
+int triaccel_stage_times_last(triaccel_handle h, triaccel_stage_times *out);
+
+/*
+ * Utility: convert n fp32 values (device) to `dtype` (device) with the same round-to-nearest-even
+ * store the update kernel uses; dtype FP32 copies.  Enqueued on `hip_stream`.  Both pointers
+ * 16-byte aligned.
+ */
+int triaccel_cast_f32(const float *src, void *dst, int64_t n, int32_t dtype, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRIACCEL_H */

@@ -1,0 +1,223 @@
+"""ctypes binding of the C ABI in ``include/triaccel.h`` -- argument marshalling only.
+
+Every step of the optimizer path runs in the HIP library; nothing is computed here.  If the
+library has not been built (``python -m paper_2508_16905_amd.build`` or ``__graft_entry__.build()``)
+or cannot be loaded, every call raises: there is no CPU fallback.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtriaccel.so")
+
+FP16, BF16, FP32 = 0, 1, 2
+N_STAGES = 6
+STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "mask", "assign", "update")
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("beta_var", C.c_float),
+        ("beta_curv", C.c_float),
+        ("tau_low", C.c_float),
+        ("tau_high", C.c_float),
+        ("tau_curv", C.c_float),
+        ("alpha", C.c_float),
+        ("sparsity_ppm", C.c_uint32),
+        ("momentum", C.c_float),
+        ("weight_decay", C.c_float),
+        ("ctrl_interval", C.c_int32),
+        ("scale_backoff", C.c_float),
+        ("scale_growth", C.c_float),
+        ("growth_interval", C.c_int32),
+        ("rho_low", C.c_double),
+        ("rho_high", C.c_double),
+        ("delta_up", C.c_int32),
+        ("delta_down", C.c_int32),
+        ("b_min", C.c_int32),
+        ("b_max", C.c_int32),
+    ]
+
+    @classmethod
+    def from_hyper(cls, hyper: dict) -> "Config":
+        cfg = cls()
+        cfg.struct_size = C.sizeof(cls)
+        for name, _ in cls._fields_[1:]:
+            setattr(cfg, name, hyper[name])
+        return cfg
+
+
+class Tensor(C.Structure):
+    _fields_ = [
+        ("param", C.c_void_p),
+        ("grad", C.c_void_p),
+        ("z", C.c_void_p),
+        ("hz", C.c_void_p),
+        ("curv", C.c_void_p),
+        ("mom", C.c_void_p),
+        ("mask", C.c_void_p),
+        ("numel", C.c_int64),
+        ("grad_dtype", C.c_int32),
+        ("param_dtype", C.c_int32),
+    ]
+
+
+class StepArgs(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("lr", C.c_float),
+        ("loss_scale", C.c_float),
+        ("batch_size", C.c_int32),
+        ("mem_used_bytes", C.c_uint64),
+        ("mem_total_bytes", C.c_uint64),
+    ]
+
+
+class StepResult(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("skipped", C.c_int32),
+        ("step_index", C.c_uint64),
+        ("next_loss_scale", C.c_float),
+        ("next_batch_size", C.c_int32),
+    ]
+
+
+class LayerInfo(C.Structure):
+    _fields_ = [
+        ("numel", C.c_int64),
+        ("mean", C.c_float),
+        ("var", C.c_float),
+        ("v", C.c_float),
+        ("theta", C.c_float),
+        ("nnz", C.c_uint32),
+        ("lambda_", C.c_float),
+        ("lambda_ctrl", C.c_float),
+        ("eta", C.c_float),
+        ("code", C.c_int32),
+        ("prev_code", C.c_int32),
+        ("found_inf", C.c_uint32),
+        ("curv_nonfinite", C.c_uint32),
+    ]
+
+
+class StageTimes(C.Structure):
+    _fields_ = [("ms", C.c_float * N_STAGES)]
+
+
+EXPORTS = {
+    "triaccel_init": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(Config), C.POINTER(Tensor), C.c_int32, C.c_void_p]),
+    "triaccel_step": (C.c_int, [C.c_void_p, C.POINTER(Tensor), C.c_int32, C.POINTER(StepArgs)]),
+    "triaccel_result": (C.c_int, [C.c_void_p, C.POINTER(StepResult)]),
+    "triaccel_layer_state": (C.c_int, [C.c_void_p, C.POINTER(LayerInfo), C.c_int32]),
+    "triaccel_batch_next": (C.c_int32, [C.POINTER(Config), C.c_int32, C.c_uint64, C.c_uint64]),
+    "triaccel_destroy": (None, [C.c_void_p]),
+    "triaccel_strerror": (C.c_char_p, [C.c_int]),
+    "triaccel_last_error": (C.c_char_p, []),
+    "triaccel_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
+    "triaccel_stage_times_last": (C.c_int, [C.c_void_p, C.POINTER(StageTimes)]),
+    "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
+}
+
+_lib: Optional[C.CDLL] = None
+
+
+class TriAccelError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = ""
+        if _lib is not None:
+            detail = _lib.triaccel_strerror(code).decode()
+            if code == -6:
+                detail += " -- " + _lib.triaccel_last_error().decode()
+        super().__init__(f"{where} failed with code {code}: {detail}")
+
+
+def load_library() -> C.CDLL:
+    """Load ``libtriaccel.so`` (built in-tree).  Raises if it is missing: no fallback exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build the HIP library first "
+            "(python -m paper_2508_16905_amd.build, or __graft_entry__.build())"
+        )
+    lib = C.CDLL(LIB_PATH)
+    for name, (res, args) in EXPORTS.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise TriAccelError(code, where)
+
+
+# ---- thin wrappers with the C names ------------------------------------------------------------
+
+def triaccel_init(config: Config, tensors: Sequence[Tensor], stream: int = 0) -> C.c_void_p:
+    lib = load_library()
+    arr = (Tensor * len(tensors))(*tensors)
+    handle = C.c_void_p()
+    _check(lib.triaccel_init(C.byref(handle), C.byref(config), arr, len(tensors), C.c_void_p(stream)), "triaccel_init")
+    return handle
+
+
+def triaccel_step(handle, tensors, lr: float, loss_scale: float, batch_size: int = 0, mem_used_bytes: int = 0,
+                  mem_total_bytes: int = 0) -> None:
+    """``tensors`` is a ctypes array ``(Tensor * n)`` or a sequence of ``Tensor``."""
+    lib = load_library()
+    arr = tensors if isinstance(tensors, C.Array) else (Tensor * len(tensors))(*tensors)
+    args = StepArgs(C.sizeof(StepArgs), lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes)
+    _check(lib.triaccel_step(handle, arr, len(arr), C.byref(args)), "triaccel_step")
+
+
+def triaccel_result(handle) -> StepResult:
+    lib = load_library()
+    res = StepResult()
+    res.struct_size = C.sizeof(StepResult)
+    _check(lib.triaccel_result(handle, C.byref(res)), "triaccel_result")
+    return res
+
+
+def triaccel_layer_state(handle, n: int):
+    lib = load_library()
+    arr = (LayerInfo * n)()
+    _check(lib.triaccel_layer_state(handle, arr, n), "triaccel_layer_state")
+    return arr
+
+
+def triaccel_batch_next(config: Config, batch_size: int, mem_used_bytes: int, mem_total_bytes: int) -> int:
+    return load_library().triaccel_batch_next(C.byref(config), batch_size, mem_used_bytes, mem_total_bytes)
+
+
+def triaccel_destroy(handle) -> None:
+    load_library().triaccel_destroy(handle)
+
+
+def triaccel_strerror(code: int) -> str:
+    return load_library().triaccel_strerror(code).decode()
+
+
+def triaccel_set_profiling(handle, on: bool) -> None:
+    _check(load_library().triaccel_set_profiling(handle, int(on)), "triaccel_set_profiling")
+
+
+def triaccel_stage_times_last(handle):
+    st = StageTimes()
+    _check(load_library().triaccel_stage_times_last(handle, C.byref(st)), "triaccel_stage_times_last")
+    return list(st.ms)
+
+
+def triaccel_cast_f32(src_ptr: int, dst_ptr: int, n: int, dtype: int, stream: int = 0) -> None:
+    _check(load_library().triaccel_cast_f32(C.c_void_p(src_ptr), C.c_void_p(dst_ptr), n, dtype, C.c_void_p(stream)),
+           "triaccel_cast_f32")

@@ -1,0 +1,443 @@
+// Host side of the C ABI declared in include/triaccel.h: argument validation, workspace,
+// pointer-table upload and the sequence of kernel launches of one optimizer step
+// (control loop of Sec. 3.4).  No device synchronisation happens inside triaccel_step.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/triaccel.h"
+#include "kernels.h"
+
+using namespace triaccel;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int hip_fail(hipError_t e, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return TRIACCEL_E_HIP;
+}
+
+#define TA_HIP(call)                                   \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) return hip_fail(e_, #call);  \
+  } while (0)
+
+constexpr int kRing = 4;  // pinned staging buffers for the pointer table
+
+bool valid_dtype(int32_t d) { return d == TRIACCEL_FP16 || d == TRIACCEL_BF16 || d == TRIACCEL_FP32; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct triaccel_ctx {
+  hipStream_t stream = nullptr;
+  int device = 0;
+  triaccel_config cfg{};
+  Hyper hp{};
+  uint32_t n = 0;
+  std::vector<int64_t> numel;
+  std::vector<int32_t> grad_dtype;
+  DeviceTables t{};
+  std::vector<TensorDesc> desc;       // host copy of the table to upload
+  std::vector<TensorDesc> desc_sent;  // what the device currently holds
+  bool desc_valid = false;
+  TensorDesc* staging[kRing] = {};
+  hipEvent_t staging_ev[kRing] = {};
+  bool staging_used[kRing] = {};
+  int ring_pos = 0;
+  GlobalDev* pinned_res = nullptr;
+  uint64_t step_index = 0;
+  int32_t next_batch = 0;
+  bool profiling = false;
+  bool times_valid = false;
+  hipEvent_t ev[TRIACCEL_N_STAGES + 1] = {};
+  std::vector<LayerDev> layer_host;
+  std::vector<void*> device_allocs;
+};
+
+namespace {
+
+template <typename T>
+int dev_alloc(triaccel_ctx* c, T** out, size_t count) {
+  void* p = nullptr;
+  const size_t bytes = (count ? count : 1) * sizeof(T);
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    g_last_error = std::string("hipMalloc: ") + hipGetErrorString(e);
+    return TRIACCEL_E_NO_MEMORY;
+  }
+  c->device_allocs.push_back(p);
+  e = hipMemset(p, 0, bytes);
+  if (e != hipSuccess) return hip_fail(e, "hipMemset");
+  *out = static_cast<T*>(p);
+  return TRIACCEL_OK;
+}
+
+int validate_config(const triaccel_config* cfg) {
+  if (!cfg) return TRIACCEL_E_NULL_PTR;
+  if (cfg->struct_size != sizeof(triaccel_config)) return TRIACCEL_E_INVALID_ARG;
+  auto unit = [](float b) { return b >= 0.0f && b < 1.0f; };
+  if (!unit(cfg->beta_var) || !unit(cfg->beta_curv)) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->tau_low <= cfg->tau_high)) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->alpha >= 0.0f) || !std::isfinite(cfg->alpha) || !std::isfinite(cfg->tau_curv)) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->sparsity_ppm > 1000000u) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->momentum >= 0.0f && cfg->momentum < 1.0f)) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->weight_decay >= 0.0f) || !std::isfinite(cfg->weight_decay)) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->ctrl_interval < 1 || cfg->growth_interval < 1) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->scale_backoff > 0.0f && cfg->scale_backoff <= 1.0f) || !(cfg->scale_growth >= 1.0f)) return TRIACCEL_E_INVALID_ARG;
+  if (!(cfg->rho_low >= 0.0 && cfg->rho_low <= cfg->rho_high && cfg->rho_high <= 1.0)) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->delta_up < 0 || cfg->delta_down < 0 || cfg->b_min < 1 || cfg->b_max < cfg->b_min) return TRIACCEL_E_INVALID_ARG;
+  return TRIACCEL_OK;
+}
+
+// Checks one tensor entry of a step (or of init, where probe pointers are not required).
+int validate_tensor(const triaccel_tensor& t, bool need_mom) {
+  if (!t.param || !t.grad || !t.curv || !t.mask) return TRIACCEL_E_NULL_PTR;
+  if (need_mom && !t.mom) return TRIACCEL_E_NULL_PTR;
+  if ((t.z == nullptr) != (t.hz == nullptr)) return TRIACCEL_E_NULL_PTR;
+  if (t.numel <= 0 || t.numel >= (int64_t(1) << 31)) return TRIACCEL_E_INVALID_ARG;
+  if (!valid_dtype(t.grad_dtype)) return TRIACCEL_E_BAD_DTYPE;
+  if (!aligned16(t.param) || !aligned16(t.grad) || !aligned16(t.curv) || !aligned16(t.mask) || !aligned16(t.mom) ||
+      !aligned16(t.z) || !aligned16(t.hz))
+    return TRIACCEL_E_ALIGNMENT;
+  return TRIACCEL_OK;
+}
+
+void free_ctx(triaccel_ctx* c) {
+  if (!c) return;
+  for (void* p : c->device_allocs) (void)hipFree(p);
+  for (int i = 0; i < kRing; ++i) {
+    if (c->staging[i]) (void)hipHostFree(c->staging[i]);
+    if (c->staging_ev[i]) (void)hipEventDestroy(c->staging_ev[i]);
+  }
+  if (c->pinned_res) (void)hipHostFree(c->pinned_res);
+  for (auto& e : c->ev)
+    if (e) (void)hipEventDestroy(e);
+  delete c;
+}
+
+int32_t batch_rule(const triaccel_config& cfg, int32_t batch, uint64_t used, uint64_t total) {
+  // Sec. 3.3: strict comparisons as printed, then the clamp.
+  const double u = (double)used, m = (double)total;
+  int64_t b = batch;
+  if (u < cfg.rho_low * m) b += cfg.delta_up;
+  else if (u > cfg.rho_high * m) b -= cfg.delta_down;
+  if (b < cfg.b_min) b = cfg.b_min;
+  if (b > cfg.b_max) b = cfg.b_max;
+  return (int32_t)b;
+}
+
+}  // namespace
+
+extern "C" {
+
+int triaccel_init(triaccel_handle* out, const triaccel_config* config, const triaccel_tensor* tensors, int32_t n,
+                  void* hip_stream) {
+  if (!out) return TRIACCEL_E_NULL_PTR;
+  *out = nullptr;
+  int rc = validate_config(config);
+  if (rc) return rc;
+  if (!tensors) return TRIACCEL_E_NULL_PTR;
+  if (n <= 0) return TRIACCEL_E_INVALID_ARG;
+  const bool need_mom = config->momentum != 0.0f;
+  uint64_t total_chunks = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    rc = validate_tensor(tensors[i], need_mom);
+    if (rc) return rc;
+    if (!valid_dtype(tensors[i].param_dtype)) return TRIACCEL_E_BAD_DTYPE;
+    total_chunks += (uint64_t)((tensors[i].numel + kChunk - 1) / kChunk);
+  }
+  if (total_chunks >= (uint64_t(1) << 31)) return TRIACCEL_E_INVALID_ARG;
+
+  triaccel_ctx* c = new (std::nothrow) triaccel_ctx();
+  if (!c) return TRIACCEL_E_NO_MEMORY;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  c->cfg = *config;
+  c->n = (uint32_t)n;
+  c->hp = Hyper{config->beta_var,     config->beta_curv,     config->tau_low,       config->tau_high,
+                config->tau_curv,     config->alpha,         config->sparsity_ppm,  config->momentum,
+                config->weight_decay, config->ctrl_interval, config->scale_backoff, config->scale_growth,
+                config->growth_interval};
+  auto fail = [&](int code) {
+    free_ctx(c);
+    return code;
+  };
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipGetDevice"));
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, c->device);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipGetDeviceProperties"));
+  const uint32_t cus = prop.multiProcessorCount > 0 ? (uint32_t)prop.multiProcessorCount : 256u;
+
+  // chunk list and per-tensor table
+  std::vector<ChunkRef> chunks;
+  chunks.reserve(total_chunks);
+  c->desc.resize(n);
+  c->numel.resize(n);
+  c->grad_dtype.resize(n);
+  c->layer_host.resize(n);
+  uint64_t cand_total = 0;
+  uint32_t max_chunks = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const triaccel_tensor& t = tensors[i];
+    const uint32_t nc = (uint32_t)((t.numel + kChunk - 1) / kChunk);
+    TensorDesc& d = c->desc[i];
+    std::memset(&d, 0, sizeof(d));
+    d.numel = t.numel;
+    d.first_chunk = (uint32_t)chunks.size();
+    d.n_chunks = nc;
+    d.grad_dtype = t.grad_dtype;
+    d.cand_offset = cand_total;
+    d.cand_cap = t.numel < (int64_t)kCandCap ? (uint32_t)t.numel : kCandCap;
+    cand_total += d.cand_cap;
+    for (uint32_t k = 0; k < nc; ++k) chunks.push_back(ChunkRef{(uint32_t)i, k});
+    if (nc > max_chunks) max_chunks = nc;
+    c->numel[i] = t.numel;
+    c->grad_dtype[i] = t.grad_dtype;
+    LayerDev& ls = c->layer_host[i];
+    std::memset(&ls, 0, sizeof(ls));
+    ls.code = ls.prev_code = t.param_dtype;
+    ls.mode = kSelHist;  // first probed step: histogram over the full key range
+    ls.win_lo = 0;
+    ls.win_shift = kFullShift;
+    ls.win_bins = kHistBins;
+  }
+  DeviceTables& T = c->t;
+  T.n_tensors = (uint32_t)n;
+  T.total_chunks = (uint32_t)chunks.size();
+  T.max_chunks_per_tensor = max_chunks;
+  T.persistent_grid = cus * 8;
+  T.fallback_grid = cus * 4;
+  if ((rc = dev_alloc(c, &T.tensors, (size_t)n))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.chunks, chunks.size()))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.partials, chunks.size()))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.layers, (size_t)n))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.glob, 1))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.hist, (size_t)n * kHistBins))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.cands, (size_t)cand_total))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.trans_list, (size_t)n * 2))) return fail(rc);
+  e = hipMemcpy(T.chunks, chunks.data(), chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(chunks)"));
+  e = hipMemcpy(T.layers, c->layer_host.data(), (size_t)n * sizeof(LayerDev), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(layers)"));
+  for (int i = 0; i < kRing; ++i) {
+    e = hipHostMalloc(reinterpret_cast<void**>(&c->staging[i]), (size_t)n * sizeof(TensorDesc), hipHostMallocDefault);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(staging)"));
+    e = hipEventCreateWithFlags(&c->staging_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipEventCreate"));
+  }
+  e = hipHostMalloc(reinterpret_cast<void**>(&c->pinned_res), sizeof(GlobalDev), hipHostMallocDefault);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(result)"));
+  std::memset(c->pinned_res, 0, sizeof(GlobalDev));
+  for (auto& ev : c->ev) {
+    e = hipEventCreate(&ev);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipEventCreate"));
+  }
+  e = hipDeviceSynchronize();
+  if (e != hipSuccess) return fail(hip_fail(e, "hipDeviceSynchronize"));
+  *out = c;
+  return TRIACCEL_OK;
+}
+
+int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, const triaccel_step_args* args) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!tensors || !args) return TRIACCEL_E_NULL_PTR;
+  if (args->struct_size != sizeof(triaccel_step_args)) return TRIACCEL_E_INVALID_ARG;
+  if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
+  if (!(args->loss_scale > 0.0f) || !std::isfinite(args->loss_scale) || !std::isfinite(args->lr))
+    return TRIACCEL_E_INVALID_ARG;
+  const bool need_mom = h->cfg.momentum != 0.0f;
+  bool any_probe = false;
+  for (int32_t i = 0; i < n; ++i) {
+    const triaccel_tensor& t = tensors[i];
+    if (t.numel != h->numel[i] || t.grad_dtype != h->grad_dtype[i]) return TRIACCEL_E_SHAPE_MISMATCH;
+    const int rc = validate_tensor(t, need_mom);
+    if (rc) return rc;
+    any_probe = any_probe || t.z != nullptr;
+  }
+  // stage (4) of the control loop: batch size from memory usage, on the host
+  uint64_t used = args->mem_used_bytes, total = args->mem_total_bytes;
+  if (total == 0) {
+    size_t free_b = 0, total_b = 0;
+    TA_HIP(hipMemGetInfo(&free_b, &total_b));
+    total = total_b;
+    used = total_b - free_b;
+  }
+  const int32_t next_batch = batch_rule(h->cfg, args->batch_size, used, total);
+  // ---- nothing below can fail on the arguments; state may now change ----
+  for (int32_t i = 0; i < n; ++i) {
+    const triaccel_tensor& t = tensors[i];
+    TensorDesc& d = h->desc[i];
+    d.param = t.param;
+    d.grad = t.grad;
+    d.z = t.z;
+    d.hz = t.hz;
+    d.curv = t.curv;
+    d.mom = need_mom ? t.mom : nullptr;
+    d.mask = t.mask;
+    d.has_probe = t.z != nullptr;
+  }
+  const size_t table_bytes = (size_t)n * sizeof(TensorDesc);
+  if (!h->desc_valid || std::memcmp(h->desc.data(), h->desc_sent.data(), table_bytes) != 0) {
+    const int slot = h->ring_pos;
+    h->ring_pos = (h->ring_pos + 1) % kRing;
+    if (h->staging_used[slot]) TA_HIP(hipEventSynchronize(h->staging_ev[slot]));
+    std::memcpy(h->staging[slot], h->desc.data(), table_bytes);
+    TA_HIP(hipMemcpyAsync(h->t.tensors, h->staging[slot], table_bytes, hipMemcpyHostToDevice, h->stream));
+    TA_HIP(hipEventRecord(h->staging_ev[slot], h->stream));
+    h->staging_used[slot] = true;
+    h->desc_sent = h->desc;
+    h->desc_valid = true;
+  }
+
+  h->step_index += 1;
+  StepScalars sc;
+  sc.lr = args->lr;
+  sc.loss_scale = args->loss_scale;
+  sc.inv_scale = 1.0f / args->loss_scale;
+  sc.step_id = (uint32_t)h->step_index;
+  const float beta_h = h->cfg.beta_curv;
+  const float omb_h = 1.0f - beta_h;
+  const DeviceTables& T = h->t;
+  hipStream_t s = h->stream;
+  const bool prof = h->profiling;
+  h->times_valid = false;
+
+  if (prof) TA_HIP(hipEventRecord(h->ev[0], s));
+  TA_HIP(launch_grad_stats(T, sc, s));
+  if (prof) TA_HIP(hipEventRecord(h->ev[1], s));
+  if (any_probe) {
+    TA_HIP(launch_curv_ema_hist(T, sc, beta_h, omb_h, s));
+    TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
+  }
+  if (prof) TA_HIP(hipEventRecord(h->ev[2], s));
+  if (any_probe) {
+    // at most three refinement rounds are ever needed (11 + 11 + 9 key bits after a missed prediction)
+    for (int round = 0; round < 3; ++round) {
+      TA_HIP(launch_hist_pass(T, sc, s));
+      TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
+    }
+  }
+  if (prof) TA_HIP(hipEventRecord(h->ev[3], s));
+  if (any_probe) {
+    TA_HIP(launch_mask(T, sc, s));
+    TA_HIP(launch_select_finish(T, sc, s));
+  }
+  if (prof) TA_HIP(hipEventRecord(h->ev[4], s));
+  TA_HIP(launch_assign(T, sc, h->hp, s));
+  if (prof) TA_HIP(hipEventRecord(h->ev[5], s));
+  TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  if (prof) {
+    TA_HIP(hipEventRecord(h->ev[6], s));
+    h->times_valid = true;
+  }
+  TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
+
+  h->next_batch = next_batch;
+  return TRIACCEL_OK;
+}
+
+int triaccel_result(triaccel_handle h, triaccel_step_result* out) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!out) return TRIACCEL_E_NULL_PTR;
+  if (out->struct_size != sizeof(triaccel_step_result)) return TRIACCEL_E_INVALID_ARG;
+  if (h->step_index == 0) return TRIACCEL_E_NOT_INITIALISED;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  out->skipped = h->pinned_res->res_skipped;
+  out->step_index = h->step_index;
+  out->next_loss_scale = h->pinned_res->res_next_scale;
+  out->next_batch_size = h->next_batch;
+  return TRIACCEL_OK;
+}
+
+int triaccel_layer_state(triaccel_handle h, triaccel_layer_info* out, int32_t n) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!out) return TRIACCEL_E_NULL_PTR;
+  if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  TA_HIP(hipMemcpy(h->layer_host.data(), h->t.layers, (size_t)n * sizeof(LayerDev), hipMemcpyDeviceToHost));
+  for (int32_t i = 0; i < n; ++i) {
+    const LayerDev& ls = h->layer_host[i];
+    triaccel_layer_info& o = out[i];
+    o.numel = h->numel[i];
+    o.mean = ls.mean;
+    o.var = ls.var;
+    o.v = ls.v;
+    o.theta = ls.theta;
+    o.nnz = ls.nnz;
+    o.lambda = ls.lambda;
+    o.lambda_ctrl = ls.lambda_ctrl;
+    o.eta = ls.eta;
+    o.code = ls.code;
+    o.prev_code = ls.prev_code;
+    o.found_inf = ls.found_inf;
+    o.curv_nonfinite = ls.curv_nonfinite;
+  }
+  return TRIACCEL_OK;
+}
+
+int32_t triaccel_batch_next(const triaccel_config* config, int32_t batch_size, uint64_t mem_used_bytes,
+                            uint64_t mem_total_bytes) {
+  if (!config) return batch_size;
+  return batch_rule(*config, batch_size, mem_used_bytes, mem_total_bytes);
+}
+
+void triaccel_destroy(triaccel_handle h) {
+  if (!h) return;
+  (void)hipStreamSynchronize(h->stream);
+  free_ctx(h);
+}
+
+const char* triaccel_strerror(int code) {
+  switch (code) {
+    case TRIACCEL_OK: return "success";
+    case TRIACCEL_E_INVALID_ARG: return "invalid argument";
+    case TRIACCEL_E_BAD_DTYPE: return "dtype code must be 0 (FP16), 1 (BF16) or 2 (FP32)";
+    case TRIACCEL_E_SHAPE_MISMATCH: return "tensor list does not match the one given at init";
+    case TRIACCEL_E_NULL_PTR: return "required pointer is NULL";
+    case TRIACCEL_E_ALIGNMENT: return "device pointer is not 16-byte aligned";
+    case TRIACCEL_E_HIP: return "HIP runtime error (see triaccel_last_error)";
+    case TRIACCEL_E_NOT_INITIALISED: return "handle not initialised or no step enqueued yet";
+    case TRIACCEL_E_NO_MEMORY: return "out of memory";
+    default: return "unknown error code";
+  }
+}
+
+const char* triaccel_last_error(void) { return g_last_error.c_str(); }
+
+int triaccel_set_profiling(triaccel_handle h, int32_t on) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  h->profiling = on != 0;
+  h->times_valid = false;
+  return TRIACCEL_OK;
+}
+
+int triaccel_stage_times_last(triaccel_handle h, triaccel_stage_times* out) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!out) return TRIACCEL_E_NULL_PTR;
+  if (!h->times_valid) return TRIACCEL_E_NOT_INITIALISED;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  for (int i = 0; i < TRIACCEL_N_STAGES; ++i) TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[i], h->ev[i + 1]));
+  return TRIACCEL_OK;
+}
+
+int triaccel_cast_f32(const float* src, void* dst, int64_t n, int32_t dtype, void* hip_stream) {
+  if (!src || !dst) return TRIACCEL_E_NULL_PTR;
+  if (n < 0) return TRIACCEL_E_INVALID_ARG;
+  if (!valid_dtype(dtype)) return TRIACCEL_E_BAD_DTYPE;
+  if (!aligned16(src) || !aligned16(dst)) return TRIACCEL_E_ALIGNMENT;
+  if (n == 0) return TRIACCEL_OK;
+  TA_HIP(launch_cast(src, dst, n, dtype, static_cast<hipStream_t>(hip_stream)));
+  return TRIACCEL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Structures and constants shared by the host API and the gfx950 kernels.
+#pragma once
+#include <stdint.h>
+
+namespace triaccel {
+
+// Work decomposition: every tensor is cut into chunks of kChunk elements; a chunk is what one
+// 256-thread workgroup (4 wavefronts of 64) streams per iteration: 4 rows of 256 lanes x 4
+// consecutive elements, i.e. four coalesced 128-bit loads per lane and array.
+constexpr int kThreads = 256;
+constexpr int kVec = 4;
+constexpr int kRows = 4;
+constexpr int kRowElems = kThreads * kVec;   // 1024
+constexpr int kChunk = kRowElems * kRows;    // 4096
+constexpr int kWave = 64;
+
+// Radix-select parameters: magnitudes are 31-bit keys (sign bit cleared).
+constexpr int kHistBins = 2048;
+constexpr int kHistBits = 11;
+constexpr uint32_t kFullShift = 20;          // 2048 bins of 2^20 keys cover all 2^31 keys
+constexpr uint32_t kPredShift = 9;           // predicted window: 2048 bins of 512 keys around last theta
+constexpr uint32_t kCandCap = 32768;         // candidate-list capacity per tensor (entries)
+
+enum SelMode : uint32_t {
+  kSelHist = 0,   // a histogram over the window is (being) accumulated; the scan decides what next
+  kSelCand = 1,   // theta lies in [rng_lo, rng_hi): few enough keys there to list them
+  kSelExact = 2,  // theta is known exactly
+};
+
+struct Hyper {
+  float beta_var, beta_curv, tau_low, tau_high, tau_curv, alpha;
+  uint32_t sparsity_ppm;
+  float momentum, weight_decay;
+  int32_t ctrl_interval;
+  float scale_backoff, scale_growth;
+  int32_t growth_interval;
+};
+
+// Per-step scalars handed to the kernels.
+struct StepScalars {
+  float lr;
+  float loss_scale;
+  float inv_scale;   // 1.0f / loss_scale, one fp32 division on the host
+  uint32_t step_id;  // 1-based count of triaccel_step calls (wraps after 2^32)
+};
+
+// Device table, one entry per tensor; re-uploaded when a pointer changes.
+struct TensorDesc {
+  void* param;
+  const void* grad;
+  const float* z;
+  const float* hz;
+  float* curv;
+  float* mom;
+  uint32_t* mask;
+  int64_t numel;
+  uint32_t first_chunk;  // index of the tensor's first chunk in the global chunk list
+  uint32_t n_chunks;
+  int32_t grad_dtype;
+  int32_t has_probe;
+  uint64_t cand_offset;  // first entry of the tensor's candidate list in the pool
+  uint32_t cand_cap;     // min(numel, kCandCap)
+  uint32_t pad_;
+};
+
+// Per-layer device state.  The leading part mirrors triaccel_layer_info.
+struct LayerDev {
+  // reported
+  float mean, var, v, theta;
+  uint32_t nnz;
+  float lambda, lambda_ctrl, eta;
+  int32_t code, prev_code;
+  uint32_t found_inf, curv_nonfinite;
+  // bookkeeping
+  uint32_t applied_steps;  // steps that were not skipped
+  uint32_t probes_seen;
+  uint32_t found_epoch;    // step_id at which a non-finite gradient element was last seen
+  // threshold selection
+  uint32_t theta_key;      // |theta| bit pattern
+  uint32_t mode;           // SelMode
+  uint32_t win_lo, win_shift, win_bins;  // histogram window: bin = (key - win_lo) >> win_shift
+  uint32_t predicted;      // the window was centred on the previous theta
+  uint32_t passes;         // scans done in this step (0 = the first histogram has not been scanned yet)
+  uint32_t k_rem;          // rank still to resolve inside [rng_lo, rng_hi) (1 = largest)
+  uint32_t above;          // non-zero keys known to lie above the window / range
+  uint32_t rng_lo, rng_hi; // candidate range (kSelCand)
+  uint32_t sel_count;      // keys equal to theta (kSelExact) or inside the range (kSelCand)
+  uint32_t nonzero;        // number of non-zero keys
+  // accumulators filled by atomics during a step and cleared by the kernel that consumes them
+  uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite, cand_count;
+};
+
+// Small global record (device), copied to pinned host memory at the end of a step.
+struct GlobalDev {
+  uint32_t skip_epoch;     // == step_id when the step must be skipped
+  int32_t good_steps;      // consecutive applied steps since the last loss-scale change
+  uint32_t trans_count[2]; // number of tensors whose storage size changes (double-buffered by step parity)
+  // result record
+  int32_t res_skipped;
+  float res_next_scale;
+  uint32_t res_step_id;
+  uint32_t pad_;
+};
+
+struct ChunkRef {
+  uint32_t tensor;
+  uint32_t index;  // chunk number inside the tensor
+};
+
+struct Candidate {
+  uint32_t idx;
+  uint32_t key;
+};
+
+struct StatPartial {
+  double mean;
+  double m2;
+};
+
+}  // namespace triaccel

@@ -1,0 +1,37 @@
+// Host-callable launchers of the gfx950 kernels (defined in kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+
+namespace triaccel {
+
+// Device pointers and sizes of a handle's workspace.
+struct DeviceTables {
+  TensorDesc* tensors;
+  ChunkRef* chunks;
+  StatPartial* partials;
+  LayerDev* layers;
+  GlobalDev* glob;
+  uint32_t* hist;        // n_tensors x kHistBins
+  Candidate* cands;      // pool, sum of cand_cap entries
+  uint32_t* trans_list;  // 2 x n_tensors
+  uint32_t n_tensors;
+  uint32_t total_chunks;
+  uint32_t max_chunks_per_tensor;
+  uint32_t persistent_grid;  // workgroups of the persistent streaming kernels
+  uint32_t fallback_grid;    // workgroups of the rarely-needed passes
+};
+
+hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
+hipError_t launch_curv_ema_hist(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
+hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
+hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s);
+hipError_t launch_mask(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
+hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
+hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
+hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
+hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
+hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s);
+
+}  // namespace triaccel

@@ -1,0 +1,99 @@
+"""Convenience wrapper that holds PyTorch-ROCm tensors and hands their device pointers to the
+C ABI.  PyTorch is used for device memory and the stream only; no arithmetic happens here."""
+
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+_TORCH_DTYPE = {B.FP16: torch.float16, B.BF16: torch.bfloat16, B.FP32: torch.float32}
+_CODE = {v: k for k, v in _TORCH_DTYPE.items()}
+
+
+class TriAccel:
+    """State of one optimizer instance: per tensor a 4*numel-byte parameter buffer, curvature EMA,
+    momentum buffer and bit mask, all on the GPU."""
+
+    def __init__(self, hyper: dict, params: Sequence[torch.Tensor], grad_dtype: int = B.FP32,
+                 stream: Optional[torch.cuda.Stream] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("TriAccel needs a GPU: the optimizer step runs only in the HIP library")
+        B.load_library()
+        self.hyper = dict(hyper)
+        self.config = B.Config.from_hyper(hyper)
+        self.device = params[0].device
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.n = len(params)
+        self.numel = [int(p.numel()) for p in params]
+        self.grad_dtype = int(grad_dtype)
+        self.init_codes = [_CODE[p.dtype] for p in params]
+        self.buf: List[torch.Tensor] = []
+        for p, n in zip(params, self.numel):
+            raw = torch.zeros(4 * n, dtype=torch.uint8, device=self.device)
+            raw.view(p.dtype)[:n].copy_(p.reshape(-1))
+            self.buf.append(raw)
+        use_mom = hyper["momentum"] != 0.0
+        self.curv = [torch.zeros(n, dtype=torch.float32, device=self.device) for n in self.numel]
+        self.mom = [torch.zeros(n, dtype=torch.float32, device=self.device) if use_mom else None for n in self.numel]
+        self.mask = [torch.zeros((n + 31) // 32, dtype=torch.int32, device=self.device) for n in self.numel]
+        self._tensors = (B.Tensor * self.n)()
+        for i in range(self.n):
+            t = self._tensors[i]
+            t.param = self.buf[i].data_ptr()
+            t.curv = self.curv[i].data_ptr()
+            t.mom = self.mom[i].data_ptr() if use_mom else None
+            t.mask = self.mask[i].data_ptr()
+            t.numel = self.numel[i]
+            t.grad_dtype = self.grad_dtype
+            t.param_dtype = self.init_codes[i]
+        # init validates grad pointers too: give it any valid address (the parameter buffer)
+        for i in range(self.n):
+            self._tensors[i].grad = self.buf[i].data_ptr()
+        torch.cuda.synchronize(self.device)
+        self.handle = B.triaccel_init(self.config, self._tensors, self.stream.cuda_stream)
+        self._keep = None
+
+    def step(self, grads: Sequence[torch.Tensor], zs: Optional[Sequence[Optional[torch.Tensor]]] = None,
+             hzs: Optional[Sequence[Optional[torch.Tensor]]] = None, lr: float = 0.1, loss_scale: float = 1.0,
+             batch_size: int = 0, mem_used_bytes: int = 0, mem_total_bytes: int = 0) -> None:
+        """Enqueue one step (asynchronous).  The caller keeps ``grads``/``zs``/``hzs`` alive until
+        the stream has passed the step; a reference is also held here until the next call."""
+        for i in range(self.n):
+            t = self._tensors[i]
+            t.grad = grads[i].data_ptr()
+            z = None if zs is None else zs[i]
+            t.z = None if z is None else z.data_ptr()
+            t.hz = None if z is None else hzs[i].data_ptr()
+        self._keep = (grads, zs, hzs)
+        B.triaccel_step(self.handle, self._tensors, lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes)
+
+    def result(self) -> B.StepResult:
+        return B.triaccel_result(self.handle)
+
+    def layer_state(self):
+        return B.triaccel_layer_state(self.handle, self.n)
+
+    def param(self, i: int, code: int) -> torch.Tensor:
+        """View of tensor ``i``'s stored parameters as precision ``code`` (take it from layer_state)."""
+        return self.buf[i].view(_TORCH_DTYPE[code])[: self.numel[i]]
+
+    def set_profiling(self, on: bool) -> None:
+        B.triaccel_set_profiling(self.handle, on)
+
+    def stage_times(self):
+        return B.triaccel_stage_times_last(self.handle)
+
+    def close(self) -> None:
+        if self.handle is not None:
+            B.triaccel_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import get_workload
+from workloads.configs import BF16, FP16, FP32, Workload, _DEFAULT_HYPER
+from _gpu_harness import Pair
+
+pytestmark = pytest.mark.gpu
+
+
+def custom(sizes, name="resnet18", grad_dtype=FP32, param_dtypes=None, steps=4, seed=77, **hyper):
+    hp = dict(_DEFAULT_HYPER)
+    hp.update(sparsity_ppm=950000, tau_low=1e-6, tau_high=3e-5, tau_curv=0.1)
+    hp.update(hyper)
+    tensors = [(f"t{i}", (n,)) for i, n in enumerate(sizes)]
+    kind = "student_t" if name in ("resnet18", "efficientnet_b0") else "normal"
+    return Workload(name, 1, tensors, hp, steps, grad_dtype=grad_dtype, param_dtypes=param_dtypes,
+                    grad_kind=kind, seed=seed)
+
+
+def test_tiny_mlp_all_steps():
+    wl = get_workload("tiny_mlp")
+    p = Pair(wl).run(wl.steps)
+    assert {c for row in p.code_hist for c in row} == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_ragged_sizes_and_tile_edges():
+    # sizes around every granularity of the kernels: vector (4), mask word (32), row (1024),
+    # chunk (4096), several chunks plus a ragged tail, candidate capacity (32768)
+    sizes = [1, 2, 3, 4, 5, 31, 32, 33, 63, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 12289, 32767, 32768,
+             32769, 70001, 300007]
+    wl = custom(sizes, steps=6)
+    Pair(wl).run(6).close()
+
+
+def test_resnet18_shaped_set():
+    wl = get_workload("resnet18")
+    p = Pair(wl).run(12)
+    assert {c for row in p.code_hist for c in row} == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_efficientnet_b0_shaped_set_with_loss_scale():
+    wl = get_workload("efficientnet_b0")
+    p = Pair(wl).run(12)
+    assert {c for row in p.code_hist for c in row} == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_large_streaming_scaled_down():
+    wl = get_workload("large_streaming", n_tensors=6, side=512)
+    Pair(wl).run(8).close()
+
+
+def test_mixed_state_scaled_down_overflow_and_loss_scale():
+    wl = get_workload("mixed_state", n_square=4, n_wide=8, rows=64)
+    p = Pair(wl)
+    skipped = []
+    for t in range(1, 31):
+        g, z, hz = p.inputs(t)
+        skipped.append(p.step(g, z, hz)["skipped"])
+    assert sum(skipped) >= 4 and skipped[6] == 1 and skipped[13] == 1
+    assert {c for row in p.code_hist for c in row} == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_probe_every_third_step_and_control_interval():
+    wl = custom([5000, 70000, 33], steps=10, ctrl_interval=3)
+    Pair(wl).run(10, probe_every=3).close()
+
+
+def test_no_momentum_buffer():
+    wl = custom([4097, 100], momentum=0.0)
+    Pair(wl).run(4).close()
+
+
+@pytest.mark.parametrize("gd", [FP16, BF16])
+def test_half_precision_gradients(gd):
+    wl = custom([4097, 100, 40000], grad_dtype=gd, loss_scale=1024.0)
+    Pair(wl).run(4).close()
+
+
+def test_every_precision_transition_in_place():
+    # initial dtypes x codes forced by the thresholds: each run sends all tensors to one code
+    sizes = [1, 7, 4096, 4097, 8192, 8193, 20000, 140000]
+    for target, (lo, hi) in {FP16: (1e30, 1e31), BF16: (0.0, 1e30), FP32: (0.0, 0.0)}.items():
+        for init in (FP16, BF16, FP32):
+            wl = custom(sizes, param_dtypes=[init] * len(sizes), tau_low=lo, tau_high=hi, tau_curv=1e30)
+            p = Pair(wl).run(3)
+            assert all(c == target for c in p.code_hist[-1])
+            p.close()
+
+
+def test_codes_switching_every_step():
+    # variance EMA disabled (beta = 0) and a gradient scale that cycles over three decades: codes move
+    # between all three precisions from step to step, exercising narrowing and widening repeatedly
+    sizes = [9000, 4096, 130000, 50]
+    wl = custom(sizes, name="large_streaming", beta_var=0.0, tau_low=1e-4, tau_high=1e-2, tau_curv=1e30)
+    p = Pair(wl)
+    mult = [0.1, 1.0, 10.0, 10.0, 0.1, 1.0, 0.1, 10.0]
+    for t, m in enumerate(mult, start=1):
+        g, z, hz = p.inputs(t)
+        p.step([x * (m * 3.0) for x in g], z, hz)
+    seq = [row[0] for row in p.code_hist]
+    assert set(seq) == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_degenerate_curvature_values():
+    sizes = [50000, 4097, 64]
+    wl = custom(sizes, steps=3)
+    p = Pair(wl)
+    n = wl.n_tensors
+    g, z, hz = p.inputs(1)
+    # step 1: zero probe -> h = 0 everywhere: theta = 0, empty mask
+    p.step(g, z, [torch.zeros_like(h) for h in hz], label="all-zero curvature")
+    assert all(t.nnz == 0 for t in p.orc.tensors)
+    # step 2: constant curvature -> all magnitudes tie (more ties than the candidate list holds)
+    g, z, _ = p.inputs(2)
+    p.step(g, z, [zz * 3.0 for zz in z], label="all-equal curvature")
+    # step 3: a few large entries, the rest zero: fewer non-zeros than k
+    g, z, hz = p.inputs(3)
+    sparse = []
+    for zz in z:
+        h = torch.zeros_like(zz)
+        h[:: max(1, zz.numel() // 7)] = 1000.0
+        sparse.append(h * zz)
+    p.step(g, z, sparse, label="sparse curvature")
+    # step 4: back to ordinary data (the predicted window now misses)
+    g, z, hz = p.inputs(4)
+    p.step(g, z, hz, label="after degenerate")
+    p.close()
+
+
+def test_curvature_scale_jumps_make_the_predicted_window_miss():
+    wl = custom([200000, 40000], steps=6, beta_curv=0.0)
+    p = Pair(wl)
+    for t, m in enumerate([1.0, 1.0, 1e4, 1e-6, 1.0, 1.0], start=1):
+        g, z, hz = p.inputs(t)
+        p.step(g, z, [h * m for h in hz], label=f"probe x{m}")
+    p.close()
+
+
+def test_nonfinite_probe_elements_freeze_the_element():
+    wl = custom([5000, 33])
+    p = Pair(wl)
+    g, z, hz = p.inputs(1)
+    p.step(g, z, hz)
+    g, z, hz = p.inputs(2)
+    hz[0][17] = float("inf")
+    hz[0][4999] = float("nan")
+    hz[1][32] = float("-inf")
+    p.step(g, z, hz, label="non-finite probe")
+    assert [t.curv_nonfinite for t in p.orc.tensors] == [1, 1]
+    g, z, hz = p.inputs(3)
+    p.step(g, z, hz)
+    assert [t.curv_nonfinite for t in p.orc.tensors] == [0, 0]
+    p.close()
+
+
+@pytest.mark.parametrize("bad", [float("inf"), float("-inf"), float("nan")])
+def test_skip_step_leaves_all_state_untouched(bad):
+    wl = custom([5000, 33, 4096])
+    p = Pair(wl).run(2)
+    before = [(p.gpu.buf[l].clone(), p.gpu.curv[l].clone(), p.gpu.mom[l].clone(), p.gpu.mask[l].clone())
+              for l in range(wl.n_tensors)]
+    g, z, hz = p.inputs(3)
+    g[2][4095] = bad
+    res = p.step(g, z, hz, label="overflow")
+    assert res["skipped"] == 1
+    for l, (b, c, m, k) in enumerate(before):
+        assert torch.equal(b, p.gpu.buf[l]) and torch.equal(c, p.gpu.curv[l])
+        assert torch.equal(m, p.gpu.mom[l]) and torch.equal(k, p.gpu.mask[l])
+    g, z, hz = p.inputs(3)
+    assert p.step(g, z, hz)["skipped"] == 0
+    p.close()
+
+
+def test_large_variance_offset():
+    # Var[x + c] at c = 1e4 sigma: a single-pass fp32 reduction would lose the variance entirely
+    wl = custom([300000, 5000], name="large_streaming", tau_curv=1e30)
+    p = Pair(wl)
+    for t in (1, 2):
+        g, z, hz = p.inputs(t)
+        sigma = wl.layer_consts(0)["sigma"]
+        p.step([x + 1e4 * sigma for x in g], z, hz, label="offset gradients")
+    p.close()

@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Tri-Accel optimizer step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all-fp32]
+
+One "step" is one pass of the whole hot path (gradient statistics, curvature EMA, threshold and
+mask, per-layer assignment, update + cast) over every tensor of the workload, with inputs already
+resident in HBM.  Prints ONE JSON line: whole-step throughput in params/s, the HBM roofline of the
+dominant kernel (update + cast) from HIP-event timings taken inside the timed region, per-stage
+figures, and the CPU oracle timed on a bounded sample of the same workload as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(numel, grad_size, prev_codes, codes, probed, momentum):
+    """Bytes each stage must move for one step, from the definitions of the stages:
+    statistics read g; the EMA reads z, Hz, h and writes h; the mask pass re-reads h and writes one
+    bit per element; the update reads g, the stored parameter and m, and writes the parameter and m."""
+    size = lambda c: 4 if c == 2 else 2
+    b = dict(grad_stats=0, curv_ema_hist=0, mask=0, update=0, update_resize=0)
+    for n, pc, c in zip(numel, prev_codes, codes):
+        b["grad_stats"] += n * grad_size
+        if probed:
+            b["curv_ema_hist"] += n * 16
+            b["mask"] += n * 4 + n / 8.0
+        upd = n * (grad_size + size(pc) + size(c) + (8 if momentum else 0))
+        b["update" if size(pc) == size(c) else "update_resize"] += upd
+    return b
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large_streaming")
+    ap.add_argument("--all-fp32", action="store_true", help="thresholds that keep every layer in FP32")
+    ap.add_argument("--input-sets", type=int, default=6, help="distinct pre-generated input batches (cycled)")
+    ap.add_argument("--cpu-sample-tensors", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the step shards by whole tensors, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    if args.steps < 1 or args.steps > 63:
+        print("bench.py: --steps must be in 1..63 (stage timings are kept for the last 64 steps)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2508_16905_amd as ta
+    from workloads import get_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = get_workload(args.workload)
+    hyper = dict(wl.hyper)
+    if args.all_fp32:
+        hyper.update(tau_low=0.0, tau_high=0.0)
+    K, W = args.steps, args.warmup
+    L, N = wl.n_tensors, wl.total_params
+    numel = [wl.numel(l) for l in range(L)]
+    grad_size = 4 if wl.grad_dtype == 2 else 2
+    scale = float(hyper["loss_scale"])
+
+    params = [wl.init_param(l, device=dev) for l in range(L)]
+    opt = ta.TriAccel(hyper, params, grad_dtype=wl.grad_dtype)
+    del params
+    R = max(1, min(args.input_sets, K + W))
+    sets = []
+    for r in range(R):
+        grads = [wl.grad(r + 1, l, scale, device=dev) for l in range(L)]
+        pr = [wl.probe(r + 1, l, scale, device=dev) for l in range(L)]
+        sets.append((grads, [p[0] for p in pr], [p[1] for p in pr]))
+    torch.cuda.synchronize()
+    print(f"[bench] {wl.name}: {L} tensors, {N} params, {R} input sets resident, "
+          f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated", file=sys.stderr, flush=True)
+
+    opt.set_profiling(True)
+    lr = float(hyper["lr"])
+
+    def one(i):
+        g, z, hz = sets[i % R]
+        opt.step(g, z, hz, lr=lr, loss_scale=scale, batch_size=int(hyper["batch_size"]),
+                 mem_used_bytes=8, mem_total_bytes=10)
+
+    for i in range(W):
+        one(i)
+    res = opt.result()
+    assert not res.skipped
+    codes_before = [s.code for s in opt.layer_state()]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        one(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    res = opt.result()
+    assert not res.skipped and res.step_index == W + K
+    state = opt.layer_state()
+    codes = [s.code for s in state]
+    prev_codes = [s.prev_code for s in state]
+    stage_ms = [[0.0] * len(ta.STAGE_NAMES) for _ in range(K)]
+    for back in range(K):
+        stage_ms[K - 1 - back] = opt.stage_times(back)
+    mean_ms = {name: sum(s[i] for s in stage_ms) / K for i, name in enumerate(ta.STAGE_NAMES)}
+
+    # algorithmic traffic of the last timed step (codes are stationary over the timed region
+    # unless a layer switched; the count of switches is reported)
+    switched = sum(1 for a, b in zip(codes_before, codes) if a != b)
+    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, True, hyper["momentum"] != 0.0)
+    total_bytes = sum(alg.values())
+    stages = {}
+    for name in ta.STAGE_NAMES:
+        entry = {"ms": round(mean_ms[name], 4)}
+        if alg.get(name):
+            entry["alg_GB"] = round(alg[name] / 1e9, 4)
+            entry["GBps"] = round(alg[name] / 1e9 / (mean_ms[name] / 1e3), 1) if mean_ms[name] > 0 else None
+        stages[name] = entry
+    upd_gbps = alg["update"] / 1e9 / (mean_ms["update"] / 1e3)
+    step_gbps = total_bytes / 1e9 / (ms_per_step / 1e3)
+
+    out = {
+        "metric": "fused Tri-Accel step throughput (params/s; achieved HBM GB/s in roofline)",
+        "value": N / (ms_per_step / 1e3),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: {L} tensors, {N} params, fp{8 * grad_size} gradients, probe every step, "
+                        f"momentum {hyper['momentum']}, sparsity {hyper['sparsity_ppm'] / 1e4:.0f}%",
+            "all_fp32": bool(args.all_fp32),
+            "codes": {"fp16": codes.count(0), "bf16": codes.count(1), "fp32": codes.count(2)},
+            "layers_switched_in_timed_region": switched,
+            "input_sets": R,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "k_update (fused update + cast)",
+            "achieved": upd_gbps,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": upd_gbps / HBM_PEAK_GBPS,
+            "traffic": None,
+        },
+        "step": {
+            "alg_bytes_per_param": total_bytes / N,
+            "alg_GB": total_bytes / 1e9,
+            "GBps": step_gbps,
+            "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
+        },
+        "stages": stages,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, hyper, sets[0], args.cpu_sample_tensors, scale)
+    opt.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, hyper, first_set, n_sample, scale):
+    """The CPU oracle, as it stands, timed on the first tensors of the same workload for one step."""
+    import oracle
+    from _runner import to_numpy
+
+    idx = list(range(min(n_sample, wl.n_tensors)))
+    # bound the sample to about 1.5e8 parameters
+    while len(idx) > 1 and sum(wl.numel(l) for l in idx) > 150_000_000:
+        idx.pop()
+    cores = max(1, min(len(idx), 16, os.cpu_count() or 1))
+    cfg = oracle.OracleConfig.from_hyper(hyper)
+    params = [to_numpy(wl.init_param(l)) for l in idx]
+    orc = oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx),
+                                workers=cores)
+    g = [to_numpy(first_set[0][l]) for l in idx]
+    z = [to_numpy(first_set[1][l]) for l in idx]
+    hz = [to_numpy(first_set[2][l]) for l in idx]
+    t0 = time.perf_counter()
+    orc.step(g, z, hz, float(hyper["lr"]), scale, int(hyper["batch_size"]), 8, 10)
+    dt = time.perf_counter() - t0
+    n = sum(wl.numel(l) for l in idx)
+    return {
+        "value": n / dt,
+        "unit": "params/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"first {len(idx)} tensors ({n} params) of the workload, 1 step, {dt:.2f} s wall",
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -125,11 +125,14 @@ typedef struct {
   uint32_t curv_nonfinite; /* a probe sample was non-finite at the last probed step (element frozen) */
 } triaccel_layer_info;
 
-/* Stage timings of the last step (only filled while profiling is on). */
-#define TRIACCEL_N_STAGES 6
+/* Stage timings of one step (only recorded while profiling is on). */
+#define TRIACCEL_N_STAGES 7
+#define TRIACCEL_PROFILE_RING 64
 typedef struct {
-  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram, 2 threshold
-                                  refinement passes, 3 mask, 4 per-layer assign, 5 update + cast   */
+  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram (+ first scan),
+                                  2 threshold refinement passes, 3 mask (+ candidate resolution),
+                                  4 per-layer assign, 5 update + cast of tensors whose storage size
+                                  is unchanged, 6 phased in-place update of tensors whose size changes */
 } triaccel_stage_times;
 
 /*
@@ -170,8 +173,11 @@ const char *triaccel_last_error(void);
 /* Record HIP events between the stages of every following step (on != 0) or stop doing so. */
 int triaccel_set_profiling(triaccel_handle h, int32_t on);
 
-/* Wait for the last step and return its stage timings; needs profiling on. */
-int triaccel_stage_times_last(triaccel_handle h, triaccel_stage_times *out);
+/*
+ * Wait for the stream and return the stage timings of the step enqueued `steps_back` calls ago
+ * (0 = the last one; at most TRIACCEL_PROFILE_RING - 1).  That step must have run with profiling on.
+ */
+int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_stage_times *out);
 
 /*
  * Utility: convert n fp32 values (device) to `dtype` (device) with the same round-to-nearest-even

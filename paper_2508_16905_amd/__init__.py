@@ -24,7 +24,7 @@ from .binding import (  # noqa: F401
     triaccel_layer_state,
     triaccel_result,
     triaccel_set_profiling,
-    triaccel_stage_times_last,
+    triaccel_stage_times_get,
     triaccel_step,
     triaccel_strerror,
 )

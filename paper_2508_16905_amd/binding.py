@@ -15,8 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtriaccel.so")
 
 FP16, BF16, FP32 = 0, 1, 2
-N_STAGES = 6
-STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "mask", "assign", "update")
+N_STAGES = 7
+STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "mask", "assign", "update", "update_resize")
 
 
 class Config(C.Structure):
@@ -120,7 +120,7 @@ EXPORTS = {
     "triaccel_strerror": (C.c_char_p, [C.c_int]),
     "triaccel_last_error": (C.c_char_p, []),
     "triaccel_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
-    "triaccel_stage_times_last": (C.c_int, [C.c_void_p, C.POINTER(StageTimes)]),
+    "triaccel_stage_times_get": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(StageTimes)]),
     "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
 }
 
@@ -212,9 +212,9 @@ def triaccel_set_profiling(handle, on: bool) -> None:
     _check(load_library().triaccel_set_profiling(handle, int(on)), "triaccel_set_profiling")
 
 
-def triaccel_stage_times_last(handle):
+def triaccel_stage_times_get(handle, steps_back: int = 0):
     st = StageTimes()
-    _check(load_library().triaccel_stage_times_last(handle, C.byref(st)), "triaccel_stage_times_last")
+    _check(load_library().triaccel_stage_times_get(handle, steps_back, C.byref(st)), "triaccel_stage_times_get")
     return list(st.ms)
 
 

@@ -57,8 +57,8 @@ struct triaccel_ctx {
   uint64_t step_index = 0;
   int32_t next_batch = 0;
   bool profiling = false;
-  bool times_valid = false;
-  hipEvent_t ev[TRIACCEL_N_STAGES + 1] = {};
+  hipEvent_t ev[TRIACCEL_PROFILE_RING][TRIACCEL_N_STAGES + 1] = {};
+  uint64_t ev_step[TRIACCEL_PROFILE_RING] = {};  // step_index recorded in each ring slot (0 = none)
   std::vector<LayerDev> layer_host;
   std::vector<void*> device_allocs;
 };
@@ -119,8 +119,9 @@ void free_ctx(triaccel_ctx* c) {
     if (c->staging_ev[i]) (void)hipEventDestroy(c->staging_ev[i]);
   }
   if (c->pinned_res) (void)hipHostFree(c->pinned_res);
-  for (auto& e : c->ev)
-    if (e) (void)hipEventDestroy(e);
+  for (auto& set : c->ev)
+    for (auto& e : set)
+      if (e) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -237,10 +238,6 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   e = hipHostMalloc(reinterpret_cast<void**>(&c->pinned_res), sizeof(GlobalDev), hipHostMallocDefault);
   if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(result)"));
   std::memset(c->pinned_res, 0, sizeof(GlobalDev));
-  for (auto& ev : c->ev) {
-    e = hipEventCreate(&ev);
-    if (e != hipSuccess) return fail(hip_fail(e, "hipEventCreate"));
-  }
   e = hipDeviceSynchronize();
   if (e != hipSuccess) return fail(hip_fail(e, "hipDeviceSynchronize"));
   *out = c;
@@ -309,16 +306,17 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   const DeviceTables& T = h->t;
   hipStream_t s = h->stream;
   const bool prof = h->profiling;
-  h->times_valid = false;
+  hipEvent_t* ev = h->ev[h->step_index % TRIACCEL_PROFILE_RING];
+  h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = 0;
 
-  if (prof) TA_HIP(hipEventRecord(h->ev[0], s));
+  if (prof) TA_HIP(hipEventRecord(ev[0], s));
   TA_HIP(launch_grad_stats(T, sc, s));
-  if (prof) TA_HIP(hipEventRecord(h->ev[1], s));
+  if (prof) TA_HIP(hipEventRecord(ev[1], s));
   if (any_probe) {
     TA_HIP(launch_curv_ema_hist(T, sc, beta_h, omb_h, s));
     TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
   }
-  if (prof) TA_HIP(hipEventRecord(h->ev[2], s));
+  if (prof) TA_HIP(hipEventRecord(ev[2], s));
   if (any_probe) {
     // at most three refinement rounds are ever needed (11 + 11 + 9 key bits after a missed prediction)
     for (int round = 0; round < 3; ++round) {
@@ -326,19 +324,20 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
       TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
     }
   }
-  if (prof) TA_HIP(hipEventRecord(h->ev[3], s));
+  if (prof) TA_HIP(hipEventRecord(ev[3], s));
   if (any_probe) {
     TA_HIP(launch_mask(T, sc, s));
     TA_HIP(launch_select_finish(T, sc, s));
   }
-  if (prof) TA_HIP(hipEventRecord(h->ev[4], s));
+  if (prof) TA_HIP(hipEventRecord(ev[4], s));
   TA_HIP(launch_assign(T, sc, h->hp, s));
-  if (prof) TA_HIP(hipEventRecord(h->ev[5], s));
+  if (prof) TA_HIP(hipEventRecord(ev[5], s));
   TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  if (prof) TA_HIP(hipEventRecord(ev[6], s));
   TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
   if (prof) {
-    TA_HIP(hipEventRecord(h->ev[6], s));
-    h->times_valid = true;
+    TA_HIP(hipEventRecord(ev[7], s));
+    h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;
   }
   TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
 
@@ -416,17 +415,26 @@ const char* triaccel_last_error(void) { return g_last_error.c_str(); }
 
 int triaccel_set_profiling(triaccel_handle h, int32_t on) {
   if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (on) {
+    for (auto& set : h->ev)
+      for (auto& e : set)
+        if (!e) TA_HIP(hipEventCreate(&e));
+  }
   h->profiling = on != 0;
-  h->times_valid = false;
   return TRIACCEL_OK;
 }
 
-int triaccel_stage_times_last(triaccel_handle h, triaccel_stage_times* out) {
+int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_stage_times* out) {
   if (!h) return TRIACCEL_E_NOT_INITIALISED;
   if (!out) return TRIACCEL_E_NULL_PTR;
-  if (!h->times_valid) return TRIACCEL_E_NOT_INITIALISED;
+  if (steps_back < 0 || steps_back >= TRIACCEL_PROFILE_RING || (uint64_t)steps_back >= h->step_index)
+    return TRIACCEL_E_INVALID_ARG;
+  const uint64_t step = h->step_index - (uint64_t)steps_back;
+  const int slot = (int)(step % TRIACCEL_PROFILE_RING);
+  if (h->ev_step[slot] != step) return TRIACCEL_E_NOT_INITIALISED;
   TA_HIP(hipStreamSynchronize(h->stream));
-  for (int i = 0; i < TRIACCEL_N_STAGES; ++i) TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[i], h->ev[i + 1]));
+  for (int i = 0; i < TRIACCEL_N_STAGES; ++i)
+    TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[slot][i], h->ev[slot][i + 1]));
   return TRIACCEL_OK;
 }
 

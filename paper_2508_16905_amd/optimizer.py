@@ -84,8 +84,8 @@ class TriAccel:
     def set_profiling(self, on: bool) -> None:
         B.triaccel_set_profiling(self.handle, on)
 
-    def stage_times(self):
-        return B.triaccel_stage_times_last(self.handle)
+    def stage_times(self, steps_back: int = 0):
+        return B.triaccel_stage_times_get(self.handle, steps_back)
 
     def close(self) -> None:
         if self.handle is not None:

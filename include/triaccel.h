@@ -123,16 +123,19 @@ typedef struct {
   int32_t prev_code;    /* precision before the last applied step                                   */
   uint32_t found_inf;   /* this tensor's gradient held inf/NaN at the last step                     */
   uint32_t curv_nonfinite; /* a probe sample was non-finite at the last probed step (element frozen) */
+  uint32_t sel_passes;  /* diagnostic: passes over h, beyond the one that updates it, that the threshold
+                           selection of the last probed step needed (0 when the prediction held)        */
 } triaccel_layer_info;
 
 /* Stage timings of one step (only recorded while profiling is on). */
 #define TRIACCEL_N_STAGES 7
 #define TRIACCEL_PROFILE_RING 64
 typedef struct {
-  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram (+ first scan),
-                                  2 threshold refinement passes, 3 mask (+ candidate resolution),
-                                  4 per-layer assign, 5 update + cast of tensors whose storage size
-                                  is unchanged, 6 phased in-place update of tensors whose size changes */
+  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram + provisional mask
+                                  (+ first scan), 2 threshold refinement passes (fallback), 3 per-layer
+                                  assign, 4 update + cast of tensors whose storage size is unchanged
+                                  (+ fallback mask pass), 5 phased in-place update of tensors whose size
+                                  changes, 6 threshold resolution among listed keys + mask patch        */
 } triaccel_stage_times;
 
 /*

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libtriaccel.so")
 
 FP16, BF16, FP32 = 0, 1, 2
 N_STAGES = 7
-STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "mask", "assign", "update", "update_resize")
+STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "assign", "update", "update_resize", "select_finish")
 
 
 class Config(C.Structure):
@@ -103,6 +103,7 @@ class LayerInfo(C.Structure):
         ("prev_code", C.c_int32),
         ("found_inf", C.c_uint32),
         ("curv_nonfinite", C.c_uint32),
+        ("sel_passes", C.c_uint32),
     ]
 
 

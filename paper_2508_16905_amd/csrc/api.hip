@@ -198,7 +198,9 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
     d.grad_dtype = t.grad_dtype;
     d.cand_offset = cand_total;
     d.cand_cap = t.numel < (int64_t)kCandCap ? (uint32_t)t.numel : kCandCap;
-    cand_total += d.cand_cap;
+    d.sub_cap = (d.cand_cap + kCandLists - 1) / kCandLists;
+    d.list_all = t.numel <= (int64_t)kCandCap ? 1u : 0u;
+    cand_total += (uint64_t)kCandLists * d.sub_cap + d.cand_cap;
     for (uint32_t k = 0; k < nc; ++k) chunks.push_back(ChunkRef{(uint32_t)i, k});
     if (nc > max_chunks) max_chunks = nc;
     c->numel[i] = t.numel;
@@ -224,6 +226,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   if ((rc = dev_alloc(c, &T.glob, 1))) return fail(rc);
   if ((rc = dev_alloc(c, &T.hist, (size_t)n * kHistBins))) return fail(rc);
   if ((rc = dev_alloc(c, &T.cands, (size_t)cand_total))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.cand_counters, (size_t)n * (kCandLists + 1) * kCandCounterStride))) return fail(rc);
   if ((rc = dev_alloc(c, &T.trans_list, (size_t)n * 2))) return fail(rc);
   e = hipMemcpy(T.chunks, chunks.data(), chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(chunks)"));
@@ -309,6 +312,9 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   hipEvent_t* ev = h->ev[h->step_index % TRIACCEL_PROFILE_RING];
   h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = 0;
 
+  // Order of the stages.  The per-layer assignment needs only the gradient moments and
+  // lambda_l = max |h_i| (known after the EMA pass), so it runs before the threshold is final;
+  // the mask is an output that nothing in the update depends on.
   if (prof) TA_HIP(hipEventRecord(ev[0], s));
   TA_HIP(launch_grad_stats(T, sc, s));
   if (prof) TA_HIP(hipEventRecord(ev[1], s));
@@ -325,16 +331,13 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
     }
   }
   if (prof) TA_HIP(hipEventRecord(ev[3], s));
-  if (any_probe) {
-    TA_HIP(launch_mask(T, sc, s));
-    TA_HIP(launch_select_finish(T, sc, s));
-  }
-  if (prof) TA_HIP(hipEventRecord(ev[4], s));
   TA_HIP(launch_assign(T, sc, h->hp, s));
-  if (prof) TA_HIP(hipEventRecord(ev[5], s));
+  if (prof) TA_HIP(hipEventRecord(ev[4], s));
   TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
-  if (prof) TA_HIP(hipEventRecord(ev[6], s));
+  if (prof) TA_HIP(hipEventRecord(ev[5], s));
   TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  if (prof) TA_HIP(hipEventRecord(ev[6], s));
+  if (any_probe) TA_HIP(launch_select_finish(T, sc, s));
   if (prof) {
     TA_HIP(hipEventRecord(ev[7], s));
     h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;
@@ -380,6 +383,7 @@ int triaccel_layer_state(triaccel_handle h, triaccel_layer_info* out, int32_t n)
     o.prev_code = ls.prev_code;
     o.found_inf = ls.found_inf;
     o.curv_nonfinite = ls.curv_nonfinite;
+    o.sel_passes = ls.sel_passes;
   }
   return TRIACCEL_OK;
 }

@@ -13,13 +13,17 @@ constexpr int kRows = 4;
 constexpr int kRowElems = kThreads * kVec;   // 1024
 constexpr int kChunk = kRowElems * kRows;    // 4096
 constexpr int kWave = 64;
+constexpr int kFinishThreads = 1024;          // workgroup of the per-tensor threshold-resolution kernel
 
 // Radix-select parameters: magnitudes are 31-bit keys (sign bit cleared).
 constexpr int kHistBins = 2048;
 constexpr int kHistBits = 11;
 constexpr uint32_t kFullShift = 20;          // 2048 bins of 2^20 keys cover all 2^31 keys
-constexpr uint32_t kPredShift = 9;           // predicted window: 2048 bins of 512 keys around last theta
-constexpr uint32_t kCandCap = 32768;         // candidate-list capacity per tensor (entries)
+constexpr uint32_t kMinPredShift = 6;        // finest predicted window: 2048 bins of 64 keys
+constexpr uint32_t kUnknownPredErr = 1u << 16;  // assumed prediction error (keys) before any is measured
+constexpr uint32_t kCandCap = 65536;         // keys a tensor may list in total (entries)
+constexpr uint32_t kCandLists = 64;          // sub-lists per tensor (plus one overflow list)
+constexpr uint32_t kCandCounterStride = 32;  // words between list counters: one 128-byte line each
 
 enum SelMode : uint32_t {
   kSelHist = 0,   // a histogram over the window is (being) accumulated; the scan decides what next
@@ -58,8 +62,10 @@ struct TensorDesc {
   uint32_t n_chunks;
   int32_t grad_dtype;
   int32_t has_probe;
-  uint64_t cand_offset;  // first entry of the tensor's candidate list in the pool
-  uint32_t cand_cap;     // min(numel, kCandCap)
+  uint64_t cand_offset;  // first entry of the tensor's candidate lists in the pool
+  uint32_t cand_cap;     // min(numel, kCandCap): capacity of the overflow list
+  uint32_t sub_cap;      // capacity of each of the kCandLists sub-lists: ceil(cand_cap / kCandLists)
+  uint32_t list_all;     // numel <= kCandCap: every non-zero key is listed, no histogram
   uint32_t pad_;
 };
 
@@ -71,12 +77,21 @@ struct LayerDev {
   float lambda, lambda_ctrl, eta;
   int32_t code, prev_code;
   uint32_t found_inf, curv_nonfinite;
+  uint32_t sel_passes;     // passes over h beyond the EMA pass that the last probed step needed
   // bookkeeping
   uint32_t applied_steps;  // steps that were not skipped
   uint32_t probes_seen;
   uint32_t found_epoch;    // step_id at which a non-finite gradient element was last seen
   // threshold selection
-  uint32_t theta_key;      // |theta| bit pattern
+  uint32_t theta_key;      // |theta| bit pattern (scratch while a step selects, then the result)
+  uint32_t theta_key_last; // theta of the previous probed step
+  uint32_t n_theta;        // how many thresholds are known (0, 1, 2 = two or more)
+  uint32_t pred_center;    // key the window of this step was centred on
+  uint32_t pred_err;       // |theta - pred_center| of the last probed step
+  uint32_t band_lo, band_hi;  // keys in [band_lo, band_hi) are listed by the EMA kernel
+  uint32_t use_band;       // the EMA kernel writes the provisional mask and lists the band
+  uint32_t mask_done;      // the mask needs no separate pass this step
+  uint32_t window_missed;  // the predicted window did not contain theta this step
   uint32_t mode;           // SelMode
   uint32_t win_lo, win_shift, win_bins;  // histogram window: bin = (key - win_lo) >> win_shift
   uint32_t predicted;      // the window was centred on the previous theta
@@ -86,8 +101,9 @@ struct LayerDev {
   uint32_t rng_lo, rng_hi; // candidate range (kSelCand)
   uint32_t sel_count;      // keys equal to theta (kSelExact) or inside the range (kSelCand)
   uint32_t nonzero;        // number of non-zero keys
+  uint32_t dens_count, dens_shift;  // key density near theta: dens_count keys per 2^dens_shift keys
   // accumulators filled by atomics during a step and cleared by the kernel that consumes them
-  uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite, cand_count;
+  uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite;
 };
 
 // Small global record (device), copied to pinned host memory at the end of a step.

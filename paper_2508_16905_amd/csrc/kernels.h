@@ -14,7 +14,8 @@ struct DeviceTables {
   LayerDev* layers;
   GlobalDev* glob;
   uint32_t* hist;        // n_tensors x kHistBins
-  Candidate* cands;      // pool, sum of cand_cap entries
+  Candidate* cands;      // pool: per tensor kCandLists * sub_cap + cand_cap entries
+  uint32_t* cand_counters;  // n_tensors x (kCandLists + 1) counters, kCandCounterStride words apart
   uint32_t* trans_list;  // 2 x n_tensors
   uint32_t n_tensors;
   uint32_t total_chunks;
@@ -27,7 +28,6 @@ hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipSt
 hipError_t launch_curv_ema_hist(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s);
-hipError_t launch_mask(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
 hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);

@@ -62,12 +62,14 @@ __device__ __forceinline__ Moments shfl_down(const Moments& m, int o) {
 
 // ---------------------------------------------------------------------------------------------
 // Stage 1: per-chunk gradient moments and non-finite scan (Sec. 3.1, Var[grad_l(t)]).
-// One workgroup per chunk.  Each lane accumulates shifted sums of its 16 unscaled values in fp64,
-// lanes / wavefronts are merged pairwise in a fixed order, one (mean, M2) partial per chunk.
+// One workgroup per chunk.  Each lane accumulates, in fp64, the sums of (x - K) and (x - K)^2 of
+// its 16 unscaled values x = fp32(g) * inv_scale, where the shift K is the chunk's first value
+// (a sample of the data, so the sums stay small against their cancellation).  Lanes and
+// wavefronts are added in a fixed order; one (mean, M2) partial per chunk.
 // ---------------------------------------------------------------------------------------------
 template <int GD, bool FULL>
-__device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, float inv_scale, Moments& mom,
-                                            uint32_t& bad) {
+__device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, float inv_scale, double shift,
+                                            double& s1, double& s2, uint32_t& bad) {
   const int tid = threadIdx.x;
   float g[kRows][4];
 #pragma unroll
@@ -76,8 +78,6 @@ __device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, 
     if (FULL) load4<GD>(td.grad, idx, g[r]);
     else load4_guard<GD>(td.grad, idx, td.numel, 0.0f, g[r]);
   }
-  double shift = 0.0, s1 = 0.0, s2 = 0.0;
-  int cnt = 0;
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
 #pragma unroll
@@ -86,23 +86,18 @@ __device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, 
       if (FULL || idx < td.numel) {
         const float raw = g[r][i];
         bad |= ((f2u(raw) & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
-        const double x = (double)(raw * inv_scale);
-        if (cnt == 0) shift = x;
-        const double d = x - shift;
+        const double d = (double)(raw * inv_scale) - shift;
         s1 += d;
         s2 = fma(d, d, s2);
-        ++cnt;
       }
     }
   }
-  mom.n = (double)cnt;
-  if (cnt > 0) {
-    mom.mean = shift + s1 / (double)cnt;
-    mom.m2 = s2 - s1 * s1 / (double)cnt;
-  } else {
-    mom.mean = 0.0;
-    mom.m2 = 0.0;
-  }
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
 }
 
 __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __restrict__ tds,
@@ -113,28 +108,35 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
   const TensorDesc td = tds[cr.tensor];
   const int64_t base = (int64_t)cr.index * kChunk;
   const bool full = base + kChunk <= td.numel;
-  Moments mom;
+  double s1 = 0.0, s2 = 0.0;
   uint32_t bad = 0;
+  double shift;
+  switch (td.grad_dtype) {
+    case kFP32: shift = (double)(load1<kFP32>(td.grad, base) * sc.inv_scale); break;
+    case kBF16: shift = (double)(load1<kBF16>(td.grad, base) * sc.inv_scale); break;
+    default: shift = (double)(load1<kFP16>(td.grad, base) * sc.inv_scale); break;
+  }
   if (full) {
     switch (td.grad_dtype) {
-      case kFP32: stats_chunk<kFP32, true>(td, base, sc.inv_scale, mom, bad); break;
-      case kBF16: stats_chunk<kBF16, true>(td, base, sc.inv_scale, mom, bad); break;
-      default: stats_chunk<kFP16, true>(td, base, sc.inv_scale, mom, bad); break;
+      case kFP32: stats_chunk<kFP32, true>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
+      case kBF16: stats_chunk<kBF16, true>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
+      default: stats_chunk<kFP16, true>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
     }
   } else {
     switch (td.grad_dtype) {
-      case kFP32: stats_chunk<kFP32, false>(td, base, sc.inv_scale, mom, bad); break;
-      case kBF16: stats_chunk<kBF16, false>(td, base, sc.inv_scale, mom, bad); break;
-      default: stats_chunk<kFP16, false>(td, base, sc.inv_scale, mom, bad); break;
+      case kFP32: stats_chunk<kFP32, false>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
+      case kBF16: stats_chunk<kBF16, false>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
+      default: stats_chunk<kFP16, false>(td, base, sc.inv_scale, shift, s1, s2, bad); break;
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mom = merge(mom, shfl_down(mom, o));
+  s1 = wave_sum_f64(s1);
+  s2 = wave_sum_f64(s2);
   bad = wave_or(bad);
-  __shared__ Moments s_m[kThreads / kWave];
+  __shared__ double s_sum[2][kThreads / kWave];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   if (lane == 0) {
-    s_m[wave] = mom;
+    s_sum[0][wave] = s1;
+    s_sum[1][wave] = s2;
     if (bad) {
       atomicExch(&layers[cr.tensor].found_epoch, sc.step_id);
       atomicExch(&glob->skip_epoch, sc.step_id);
@@ -142,22 +144,41 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    Moments t = s_m[0];
+    double t1 = s_sum[0][0], t2 = s_sum[1][0];
 #pragma unroll
-    for (int w = 1; w < kThreads / kWave; ++w) t = merge(t, s_m[w]);
-    partials[blockIdx.x].mean = t.mean;
-    partials[blockIdx.x].m2 = t.m2;
+    for (int w = 1; w < kThreads / kWave; ++w) {
+      t1 += s_sum[0][w];
+      t2 += s_sum[1][w];
+    }
+    const int64_t left = td.numel - base;
+    const double n = (double)(left < kChunk ? left : kChunk);
+    const double m2 = t2 - t1 * t1 / n;
+    partials[blockIdx.x].mean = shift + t1 / n;
+    partials[blockIdx.x].m2 = m2 > 0.0 ? m2 : 0.0;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Histogram window helpers (radix select on 31-bit magnitude keys).
+// Threshold selection (exact k-th largest |h_i| per tensor) -- radix select on the 31-bit
+// magnitude keys, organised so that a probed step normally needs NO pass over h beyond the one
+// that creates it:
+//
+//   * The EMA kernel histograms the new keys inside a WINDOW of 2048 bins placed around the
+//     threshold predicted from the two previous steps, counts the keys above the window, writes a
+//     provisional mask (bit = key above a narrow BAND around the prediction) and lists the keys
+//     inside the band as candidates.
+//   * A scan per tensor finds the bin holding the k-th largest key.  If that bin lies inside the
+//     band, the listed candidates resolve theta exactly and only their mask bits are patched.
+//   * Otherwise (no prediction yet, prediction off, too many candidates) the tensor falls back
+//     to further histogram passes over h and a separate mask pass.
+//   * Tensors with at most kCandCap elements skip the histogram: all their non-zero keys are
+//     listed and selected from the list.
 // ---------------------------------------------------------------------------------------------
 struct Window {
   uint32_t lo, shift, bins;
 };
 
-// Flush a workgroup's LDS histogram and per-lane accumulators to the tensor's global ones.
+// Flush a workgroup's LDS histogram to the tensor's global one and clear it.
 __device__ __forceinline__ void flush_hist(uint32_t* s_hist, uint32_t bins, uint32_t* g_hist) {
   __syncthreads();
   for (uint32_t b = threadIdx.x; b < bins; b += kThreads) {
@@ -170,18 +191,132 @@ __device__ __forceinline__ void flush_hist(uint32_t* s_hist, uint32_t bins, uint
   __syncthreads();
 }
 
+// Eight consecutive lanes hold the 32 elements of one mask word: combine their 4-bit nibbles.
+// Data-parallel-primitive moves inside the wavefront (no LDS traffic): swap neighbours in a quad,
+// swap the quad's halves, then mirror the 8-lane half row (lane i reads lane 7 - i; after the first
+// two steps all four lanes of a quad agree, so the mirror brings in the other quad's value).
+#define TA_DPP_OR(v, ctrl) ((v) | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), 0xF, 0xF, true))
+__device__ __forceinline__ uint32_t gather_mask_word(uint32_t nib, int lane) {
+  uint32_t v = nib << (4 * (lane & 7));
+  v = TA_DPP_OR(v, 0xB1);   // quad_perm [1, 0, 3, 2]
+  v = TA_DPP_OR(v, 0x4E);   // quad_perm [2, 3, 0, 1]
+  v = TA_DPP_OR(v, 0x141);  // row_half_mirror
+  return v;
+}
+
+// Store the kRows mask words of a chunk: lane (8j + r) of a wavefront writes row r's word j.
+template <bool FULL>
+__device__ __forceinline__ void store_mask_words(const TensorDesc& td, int64_t base, const uint32_t word[kRows]) {
+  const int tid = threadIdx.x;
+  const int sub = tid & 7;
+  if (sub < kRows) {
+    uint32_t v = word[0];
+#pragma unroll
+    for (int r = 1; r < kRows; ++r) v = (sub == r) ? word[r] : v;
+    const int64_t widx = ((base + (int64_t)sub * kRowElems) >> 5) + (tid >> 3);
+    if (FULL || widx < ((td.numel + 31) >> 5)) td.mask[widx] = v;
+  }
+}
+
+// Candidate storage.  Each tensor owns kCandLists sub-lists of sub_cap entries plus one overflow
+// list of cand_cap entries, each with its own counter in its own 128-byte line: appends from
+// different chunks and wavefronts go to different counters, because atomics on one hot address
+// serialise.  A batch that does not fit its sub-list spills into the overflow
+// list, so nothing is lost as long as the tensor lists at most cand_cap keys in total.
+__device__ __forceinline__ uint32_t* cand_counter(uint32_t* counters, uint32_t tensor, uint32_t list) {
+  return counters + ((size_t)tensor * (kCandLists + 1) + list) * kCandCounterStride;
+}
+
+__device__ __forceinline__ void reset_cand_counters(uint32_t* counters, uint32_t tensor) {
+  if (threadIdx.x <= kCandLists) *cand_counter(counters, tensor, threadIdx.x) = 0;
+}
+
+// Append a wavefront's candidates of one chunk (flag bit e of `flags` = element e of the lane's
+// 16) with one atomic per wavefront: lanes take consecutive slots by a prefix sum.  The sub-list
+// is chosen by (chunk, wavefront), so wavefronts running at the same time use different counters.
+__device__ __forceinline__ void append_candidates(uint32_t flags, const float (&h)[kRows][4], int64_t base,
+                                                  uint32_t chunk_index, uint32_t tensor, const TensorDesc& td,
+                                                  Candidate* cands, uint32_t* counters) {
+  if (!__any(flags != 0u)) return;  // uniform over the wavefront
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const uint32_t mine = __popc(flags);
+  uint32_t incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const uint32_t t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  const uint32_t total = __shfl(incl, kWave - 1);
+  const uint32_t list = (chunk_index * (kThreads / kWave) + wave) % kCandLists;
+  uint32_t start = 0, fit = 0, ostart = 0;
+  if (lane == 0) {
+    start = atomicAdd(cand_counter(counters, tensor, list), total);
+    fit = start < td.sub_cap ? min(total, td.sub_cap - start) : 0u;
+    if (fit < total) ostart = atomicAdd(cand_counter(counters, tensor, kCandLists), total - fit);
+  }
+  start = __shfl(start, 0);
+  fit = __shfl(fit, 0);
+  ostart = __shfl(ostart, 0);
+  uint32_t rank = incl - mine;
+  Candidate* lists = cands + td.cand_offset;
+#pragma unroll
+  for (int r = 0; r < kRows; ++r) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (flags & (1u << (r * 4 + i))) {
+        const int64_t idx = base + r * kRowElems + threadIdx.x * kVec + i;
+        const Candidate c{(uint32_t)idx, f2u(h[r][i]) & 0x7fffffffu};
+        if (rank < fit) {
+          lists[(size_t)list * td.sub_cap + start + rank] = c;
+        } else {
+          const uint32_t o = ostart + (rank - fit);
+          if (o < td.cand_cap) lists[(size_t)kCandLists * td.sub_cap + o] = c;
+        }
+        ++rank;
+      }
+    }
+  }
+}
+
+// Visit every listed candidate of a tensor.  s_counts holds the kCandLists + 1 clamped counts.
+template <int NT, typename F>
+__device__ __forceinline__ void for_each_candidate(const TensorDesc& td, const Candidate* cands,
+                                                   const uint32_t* s_counts, F f) {
+  const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (uint32_t list = wave; list <= kCandLists; list += NT / kWave) {
+    const uint32_t cnt = s_counts[list];
+    const Candidate* p = cands + td.cand_offset + (size_t)list * td.sub_cap;
+    for (uint32_t j = lane; j < cnt; j += kWave) f(p[j]);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
-// Stage 2: curvature EMA (diagonal Hutchinson signal of Sec. 3.2) fused with the first
-// histogram pass of the threshold selection.  Persistent workgroups, each owning a contiguous
-// range of chunks so that the LDS histogram is flushed once per (workgroup, tensor).
+// Stage 2: curvature EMA (diagonal Hutchinson signal of Sec. 3.2) fused with the first pass of
+// the threshold selection.  Persistent workgroups, each owning a contiguous range of chunks so
+// that the LDS histogram is flushed once per (workgroup, tensor).
 // Per element, fp32:  u = (z * hz) * inv_scale;  h = u on the tensor's first probe, else
 // h = fma(beta_h, h, (1 - beta_h) * u);  a non-finite u leaves h unchanged.
 // ---------------------------------------------------------------------------------------------
+struct EmaPlan {
+  Window w;
+  uint32_t band_lo, band_hi;
+  bool first;      // first probe of the tensor: h = u
+  bool hist;       // histogram the keys inside the window
+  bool band;       // write the provisional mask and list the keys inside [band_lo, band_hi)
+  bool list_all;   // small tensor: list every non-zero key, provisional mask all zero
+};
+
+struct EmaAcc {
+  uint32_t above, zeros, maxkey, nonfin;
+};
+
 template <bool FULL>
 __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, float inv_scale, float beta_h,
-                                          float omb_h, bool first, const Window& w, uint32_t* s_hist,
-                                          uint32_t& above, uint32_t& zeros, uint32_t& maxkey, uint32_t& nonfin) {
+                                          float omb_h, const EmaPlan& pl, uint32_t* s_hist, EmaAcc& acc,
+                                          uint32_t chunk_index, uint32_t tensor, Candidate* cands,
+                                          uint32_t* counters) {
   const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
   float z[kRows][4], hz[kRows][4], h[kRows][4];
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
@@ -196,45 +331,63 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
       load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
     }
   }
+  uint32_t word[kRows];
+  uint32_t cflags = 0;
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = base + r * kRowElems + tid * kVec;
+    uint32_t nib = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float u = z[r][i] * hz[r][i];
       u = u * inv_scale;
       float hn = h[r][i];
+      const bool valid = FULL || idx + i < td.numel;
       if ((f2u(u) & 0x7f800000u) == 0x7f800000u) {
-        if (FULL || idx + i < td.numel) nonfin = 1u;
-      } else if (first) {
+        if (valid) acc.nonfin = 1u;
+      } else if (pl.first) {
         hn = u;
       } else {
         const float p = omb_h * u;
         hn = fmaf(beta_h, hn, p);
       }
       h[r][i] = hn;
-      if (FULL || idx + i < td.numel) {
+      if (valid) {
         const uint32_t key = f2u(hn) & 0x7fffffffu;
-        maxkey = max(maxkey, key);
+        acc.maxkey = max(acc.maxkey, key);
         if (key == 0u) {
-          ++zeros;
-        } else if (key >= w.lo) {
-          const uint32_t bin = (key - w.lo) >> w.shift;
-          if (bin < w.bins) atomicAdd(&s_hist[bin], 1u);
-          else ++above;
+          ++acc.zeros;
+        } else {
+          if (pl.hist && key >= pl.w.lo) {
+            const uint32_t bin = (key - pl.w.lo) >> pl.w.shift;
+            if (bin < pl.w.bins) atomicAdd(&s_hist[bin], 1u);
+            else ++acc.above;
+          }
+          if (pl.list_all) {
+            cflags |= 1u << (r * 4 + i);
+          } else if (pl.band) {
+            if (key >= pl.band_hi) nib |= 1u << i;
+            else if (key >= pl.band_lo) cflags |= 1u << (r * 4 + i);
+          }
         }
       }
     }
     if (FULL) store4<kFP32>(td.curv, idx, h[r]);
     else store4_guard<kFP32>(td.curv, idx, td.numel, h[r]);
+    if (pl.band || pl.list_all) word[r] = gather_mask_word(nib, lane);
+  }
+  if (pl.band || pl.list_all) {
+    store_mask_words<FULL>(td, base, word);
+    append_candidates(cflags, h, base, chunk_index, tensor, td, cands, counters);
   }
 }
 
 __global__ __launch_bounds__(kThreads) void k_curv_ema_hist(const TensorDesc* __restrict__ tds,
                                                             const ChunkRef* __restrict__ chunks,
                                                             uint32_t total_chunks, LayerDev* layers,
-                                                            const GlobalDev* glob, uint32_t* hist, StepScalars sc,
-                                                            float beta_h, float omb_h) {
+                                                            const GlobalDev* glob, uint32_t* hist, Candidate* cands,
+                                                            uint32_t* counters, StepScalars sc, float beta_h,
+                                                            float omb_h) {
   if (step_skipped(glob, sc.step_id)) return;
   __shared__ uint32_t s_hist[kHistBins];
   for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
@@ -243,20 +396,18 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema_hist(const TensorDesc* __
   const uint32_t c0 = blockIdx.x * per;
   const uint32_t c1 = min(c0 + per, total_chunks);
   int cur = -1;
-  bool active = false, first = false;
-  Window w{0, 0, 0};
+  bool active = false;
+  EmaPlan pl{};
+  EmaAcc acc{0, 0, 0, 0};
   TensorDesc td;
-  uint32_t above = 0, zeros = 0, maxkey = 0, nonfin = 0;
   for (uint32_t c = c0; c <= c1; ++c) {
     const bool end = (c == c1);
     const int t = end ? -2 : (int)chunks[c].tensor;
     if (t != cur) {
       if (cur >= 0 && active) {
-        flush_hist(s_hist, w.bins, hist + (size_t)cur * kHistBins);
-        above = wave_sum(above);
-        zeros = wave_sum(zeros);
-        maxkey = wave_max(maxkey);
-        nonfin = wave_or(nonfin);
+        if (pl.hist) flush_hist(s_hist, pl.w.bins, hist + (size_t)cur * kHistBins);
+        const uint32_t above = wave_sum(acc.above), zeros = wave_sum(acc.zeros);
+        const uint32_t maxkey = wave_max(acc.maxkey), nonfin = wave_or(acc.nonfin);
         if ((threadIdx.x & (kWave - 1)) == 0) {
           LayerDev& ls = layers[cur];
           if (above) atomicAdd(&ls.acc_above, above);
@@ -270,21 +421,28 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema_hist(const TensorDesc* __
       td = tds[t];
       active = td.has_probe != 0;
       const LayerDev& ls = layers[t];
-      w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
-      first = ls.probes_seen == 0;
-      above = zeros = maxkey = nonfin = 0;
+      pl.w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
+      pl.band_lo = ls.band_lo;
+      pl.band_hi = ls.band_hi;
+      pl.first = ls.probes_seen == 0;
+      pl.list_all = td.list_all != 0;
+      pl.hist = !pl.list_all;
+      pl.band = !pl.list_all && ls.use_band != 0;
+      acc = EmaAcc{0, 0, 0, 0};
     }
     if (!active) continue;
     const int64_t base = (int64_t)chunks[c].index * kChunk;
     if (base + kChunk <= td.numel)
-      ema_chunk<true>(td, base, sc.inv_scale, beta_h, omb_h, first, w, s_hist, above, zeros, maxkey, nonfin);
+      ema_chunk<true>(td, base, sc.inv_scale, beta_h, omb_h, pl, s_hist, acc, chunks[c].index, (uint32_t)cur, cands,
+                      counters);
     else
-      ema_chunk<false>(td, base, sc.inv_scale, beta_h, omb_h, first, w, s_hist, above, zeros, maxkey, nonfin);
+      ema_chunk<false>(td, base, sc.inv_scale, beta_h, omb_h, pl, s_hist, acc, chunks[c].index, (uint32_t)cur, cands,
+                       counters);
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 3a: one more histogram pass over |h| for tensors whose window still holds too many keys
+// Fallback: one more histogram pass over |h| for tensors whose window still holds too many keys
 // to list (mode kSelHist after a scan).  Same chunk ownership as stage 2; reads h only.
 // ---------------------------------------------------------------------------------------------
 template <bool FULL>
@@ -339,8 +497,7 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
       w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
       if (!active) {
         // jump over the rest of this tensor's chunks owned by this workgroup
-        const uint32_t next = td.first_chunk + td.n_chunks;
-        c = min(next, c1);
+        c = min(td.first_chunk + td.n_chunks, c1);
         continue;
       }
     }
@@ -353,16 +510,17 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
 
 // ---------------------------------------------------------------------------------------------
 // Rank search in an LDS histogram: find the bin, counted from the top, that holds the r-th
-// largest key (1 <= r <= total).  All kThreads threads call it; results are broadcast.
+// largest key (1 <= r <= total).  All NT threads of the workgroup call it; results are broadcast.
 // ---------------------------------------------------------------------------------------------
 struct BinHit {
   uint32_t bin;     // bin holding the r-th largest key
   uint32_t higher;  // number of keys in bins above it
   uint32_t count;   // keys in that bin
 };
+template <int NT>
 __device__ BinHit find_rank_from_top(const uint32_t* s_hist, uint32_t bins, uint32_t r, uint32_t* s_part,
                                      uint32_t* s_out) {
-  const uint32_t per = (bins + kThreads - 1) / kThreads;
+  const uint32_t per = (bins + NT - 1) / NT;
   const uint32_t b0 = threadIdx.x * per;
   uint32_t sum = 0;
   for (uint32_t b = b0; b < min(b0 + per, bins); ++b) sum += s_hist[b];
@@ -370,7 +528,7 @@ __device__ BinHit find_rank_from_top(const uint32_t* s_hist, uint32_t bins, uint
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t acc = 0;
-    int t = kThreads - 1;
+    int t = NT - 1;
     for (; t > 0; --t) {
       if (acc + s_part[t] >= r) break;
       acc += s_part[t];
@@ -412,38 +570,62 @@ __device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 3 scan: one workgroup per tensor reads the tensor's histogram, clears it, and decides
-// whether theta is now exact, lies in a range small enough to list, or needs a finer pass.
+// Scan: one workgroup per tensor reads the tensor's histogram, clears it, and decides whether
+// theta is now exact, lies in a range whose keys are (or can be) listed, or needs a finer pass.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __restrict__ tds, LayerDev* layers,
-                                                          const GlobalDev* glob, uint32_t* hist, StepScalars sc,
-                                                          uint32_t sparsity_ppm) {
+                                                          const GlobalDev* glob, uint32_t* hist, uint32_t* counters,
+                                                          StepScalars sc, uint32_t sparsity_ppm) {
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
   if (!td.has_probe) return;
   LayerDev& ls = layers[l];
   if (ls.mode != kSelHist) return;
+  const bool first_scan = ls.passes == 0;
+  if (td.list_all) {
+    // small tensor: every non-zero key was listed by the EMA kernel; select from the list
+    if (threadIdx.x == 0 && first_scan) {
+      const uint32_t nonzero = (uint32_t)td.numel - ls.acc_zeros;
+      ls.nonzero = nonzero;
+      ls.k_rem = topk_count(td.numel, sparsity_ppm);
+      ls.above = 0;
+      ls.mode = kSelCand;
+      ls.rng_lo = 0;
+      ls.rng_hi = 0x80000000u;
+      ls.mask_done = 1;
+      ls.passes = 1;
+    }
+    return;
+  }
   __shared__ uint32_t s_hist[kHistBins];
   __shared__ uint32_t s_part[kThreads];
   __shared__ uint32_t s_out[8];
   const uint32_t bins = ls.win_bins, lo = ls.win_lo, shift = ls.win_shift;
+  const uint32_t band_lo = ls.band_lo, band_hi = ls.band_hi;
+  const bool use_band = first_scan && ls.use_band != 0;
   uint32_t* gh = hist + (size_t)l * kHistBins;
-  uint32_t local = 0;
+  uint32_t local = 0, in_band = 0;
   for (uint32_t b = threadIdx.x; b < kHistBins; b += kThreads) {
     const uint32_t v = (b < bins) ? gh[b] : 0u;
     s_hist[b] = v;
     local += v;
+    const uint32_t key0 = lo + (b << shift);
+    if (use_band && b < bins && key0 >= band_lo && key0 < band_hi) in_band += v;
     if (v) gh[b] = 0;
   }
   local = wave_sum(local);
-  if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = local;
+  in_band = wave_sum(in_band);
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    s_part[threadIdx.x / kWave] = local;
+    s_part[4 + threadIdx.x / kWave] = in_band;
+  }
   __syncthreads();
   const uint32_t in_window = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  const uint32_t band_total = s_part[4] + s_part[5] + s_part[6] + s_part[7];
   __syncthreads();
 
   uint32_t k, above;
-  const bool first_scan = ls.passes == 0;
   if (first_scan) {
     const uint32_t nonzero = (uint32_t)td.numel - ls.acc_zeros;
     k = topk_count(td.numel, sparsity_ppm);
@@ -457,7 +639,9 @@ __global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __re
         ls.sel_count = 0;
         ls.k_rem = k;
         ls.passes = 1;
+        ls.mask_done = 0;
       }
+      reset_cand_counters(counters, l);
       return;
     }
     if (threadIdx.x == 0) ls.nonzero = nonzero;
@@ -472,46 +656,63 @@ __global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __re
       ls.win_lo = 0;
       ls.win_shift = kFullShift;
       ls.win_bins = kHistBins;
-      ls.predicted = 0;
       ls.above = 0;
       ls.k_rem = k;
       ls.passes = 1;
+      ls.mask_done = 0;
+      ls.window_missed = 1;
     }
+    if (first_scan) reset_cand_counters(counters, l);
     return;
   }
-  const BinHit hit = find_rank_from_top(s_hist, bins, k - above, s_part, s_out);
+  const BinHit hit = find_rank_from_top<kThreads>(s_hist, bins, k - above, s_part, s_out);
+  const uint32_t new_lo = lo + (hit.bin << shift);
+  const uint32_t new_hi = new_lo + (1u << shift);
+  const bool band_ok = use_band && new_lo >= band_lo && new_hi <= band_hi && band_total <= td.cand_cap;
+  if (first_scan && !band_ok) reset_cand_counters(counters, l);  // drop whatever the EMA kernel listed
   if (threadIdx.x == 0) {
     const uint32_t new_above = above + hit.higher;
-    const uint32_t new_lo = lo + (hit.bin << shift);
     ls.above = new_above;
     ls.k_rem = k;
     ls.sel_count = hit.count;
+    ls.dens_count = hit.count;
+    ls.dens_shift = shift;
     ls.passes = ls.passes + 1;
-    if (shift == 0) {
-      ls.mode = kSelExact;
-      ls.theta_key = new_lo;
-    } else if (hit.count <= td.cand_cap) {
+    if (band_ok) {
+      // the provisional mask is right outside the band and every key of the band is listed
       ls.mode = kSelCand;
       ls.rng_lo = new_lo;
-      ls.rng_hi = new_lo + (1u << shift);
+      ls.rng_hi = new_hi;
+      ls.mask_done = 1;
     } else {
-      const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
-      ls.mode = kSelHist;
-      ls.win_lo = new_lo;
-      ls.win_shift = ns;
-      ls.win_bins = 1u << (shift - ns);
+      if (first_scan) ls.mask_done = 0;
+      if (shift == 0) {
+        ls.mode = kSelExact;
+        ls.theta_key = new_lo;
+      } else if (hit.count <= td.cand_cap) {
+        ls.mode = kSelCand;
+        ls.rng_lo = new_lo;
+        ls.rng_hi = new_hi;
+      } else {
+        const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
+        ls.mode = kSelHist;
+        ls.win_lo = new_lo;
+        ls.win_shift = ns;
+        ls.win_bins = 1u << (shift - ns);
+      }
     }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 3 mask: one workgroup per chunk re-reads |h| and writes the bit mask.  Keys above the
-// candidate range are kept, keys below dropped; keys inside it are appended to the tensor's
-// candidate list and their bits are set afterwards by k_select_finish.
+// Fallback mask pass for tensors whose mask was not settled by the EMA kernel: re-reads |h| and
+// writes the bit mask.  Keys above the range are kept, keys below dropped; keys inside it are
+// listed and their bits are set afterwards by k_select_finish.  Called from k_update.
 // ---------------------------------------------------------------------------------------------
 template <bool FULL>
 __device__ __forceinline__ void mask_chunk(const TensorDesc& td, int64_t base, uint32_t mode, uint32_t theta,
-                                           uint32_t rng_lo, uint32_t rng_hi, LayerDev& ls, Candidate* cands) {
+                                           uint32_t rng_lo, uint32_t rng_hi, uint32_t chunk_index,
+                                           uint32_t tensor, Candidate* cands, uint32_t* counters) {
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   float h[kRows][4];
@@ -522,142 +723,178 @@ __device__ __forceinline__ void mask_chunk(const TensorDesc& td, int64_t base, u
     else load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
   }
   uint32_t word[kRows];
+  uint32_t cflags = 0;
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
     uint32_t nib = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t key = f2u(h[r][i]) & 0x7fffffffu;  // guarded fill 0: never kept, never listed
-      bool keep;
       if (mode == kSelExact) {
-        keep = key >= theta && key != 0u;
-      } else {
-        keep = key >= rng_hi;
-        if (key != 0u && key >= rng_lo && key < rng_hi) {
-          const uint32_t slot = atomicAdd(&ls.cand_count, 1u);
-          if (slot < td.cand_cap) cands[td.cand_offset + slot] = Candidate{(uint32_t)(idx + i), key};
-        }
+        if (key >= theta && key != 0u) nib |= 1u << i;
+      } else if (key >= rng_hi) {
+        nib |= 1u << i;
+      } else if (key != 0u && key >= rng_lo) {
+        cflags |= 1u << (r * 4 + i);
       }
-      nib |= keep ? (1u << i) : 0u;
     }
-    // eight consecutive lanes hold the 32 elements of one mask word
-    uint32_t v = nib << (4 * (lane & 7));
-    v |= (uint32_t)__shfl_xor(v, 1);
-    v |= (uint32_t)__shfl_xor(v, 2);
-    v |= (uint32_t)__shfl_xor(v, 4);
-    word[r] = v;
+    word[r] = gather_mask_word(nib, lane);
   }
-  const int64_t n_words = (td.numel + 31) >> 5;
-  const int sub = lane & 7;
-  if (sub < kRows) {
-    uint32_t v = word[0];
+  store_mask_words<FULL>(td, base, word);
+  append_candidates(cflags, h, base, chunk_index, tensor, td, cands, counters);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Finish: one workgroup per tensor resolves theta among the listed candidates (radix select in
+// LDS), sets their mask bits, publishes theta / nnz / lambda and plans the next probed step:
+// the window is centred on the threshold extrapolated from the last two, its bin width and the
+// band width follow the error the last predictions made.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t abs_diff(uint32_t a, uint32_t b) { return a > b ? a - b : b - a; }
+
+// Sum of a per-thread count over the workgroup (kFinishThreads threads); s_red holds one word per wavefront.
+__device__ __forceinline__ uint32_t finish_block_sum(uint32_t v, uint32_t* s_red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x / kWave] = v;
+  __syncthreads();
+  uint32_t t = 0;
 #pragma unroll
-    for (int r = 1; r < kRows; ++r) v = (sub == r) ? word[r] : v;
-    const int64_t widx = ((base + (int64_t)sub * kRowElems) >> 5) + (tid >> 3);
-    if (FULL || widx < n_words) td.mask[widx] = v;
-  }
+  for (int w = 0; w < kFinishThreads / kWave; ++w) t += s_red[w];
+  return t;
 }
 
-__global__ __launch_bounds__(kThreads) void k_mask(const TensorDesc* __restrict__ tds,
-                                                   const ChunkRef* __restrict__ chunks, LayerDev* layers,
-                                                   const GlobalDev* glob, Candidate* cands, StepScalars sc) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const ChunkRef cr = chunks[blockIdx.x];
-  const TensorDesc td = tds[cr.tensor];
-  if (!td.has_probe) return;
-  LayerDev& ls = layers[cr.tensor];
-  const uint32_t mode = ls.mode;
-  if (mode == kSelHist) return;  // cannot happen after the last scan; never write a mask from a stale range
-  const uint32_t theta = ls.theta_key, lo = ls.rng_lo, hi = ls.rng_hi;
-  const int64_t base = (int64_t)cr.index * kChunk;
-  if (base + kChunk <= td.numel) mask_chunk<true>(td, base, mode, theta, lo, hi, ls, cands);
-  else mask_chunk<false>(td, base, mode, theta, lo, hi, ls, cands);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Stage 3 finish: one workgroup per tensor resolves theta among the listed candidates (radix
-// select in LDS), sets their mask bits, publishes theta / nnz / lambda and prepares the
-// histogram window of the next probed step (centred on this theta).
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_select_finish(const TensorDesc* __restrict__ tds, LayerDev* layers,
-                                                            const GlobalDev* glob, const Candidate* cands,
-                                                            StepScalars sc) {
+__global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDesc* __restrict__ tds,
+                                                                  LayerDev* layers, const GlobalDev* glob,
+                                                                  const Candidate* cands, uint32_t* counters,
+                                                                  StepScalars sc) {
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
   if (!td.has_probe) return;
   LayerDev& ls = layers[l];
   __shared__ uint32_t s_hist[kHistBins];
-  __shared__ uint32_t s_part[kThreads];
+  __shared__ uint32_t s_part[kFinishThreads];
+  __shared__ uint32_t s_red[kFinishThreads / kWave];
   __shared__ uint32_t s_out[8];
-  const uint32_t mode = ls.mode;
-  uint32_t theta = ls.theta_key;
-  uint32_t nnz = ls.above + ls.sel_count;
-  if (mode == kSelExact && theta == 0u) nnz = ls.nonzero;
-  if (mode == kSelCand) {
-    const Candidate* cl = cands + td.cand_offset;
-    const uint32_t count = min(ls.cand_count, td.cand_cap);
-    uint32_t lo = ls.rng_lo;
-    uint32_t width_shift = 31u - (uint32_t)__clz(ls.rng_hi - ls.rng_lo);  // range width is a power of two
-    uint32_t r = ls.k_rem - ls.above;
-    while (width_shift > 0) {
-      const uint32_t ns = width_shift > (uint32_t)kHistBits ? width_shift - kHistBits : 0u;
-      const uint32_t bins = 1u << (width_shift - ns);
-      for (uint32_t b = threadIdx.x; b < bins; b += kThreads) s_hist[b] = 0;
-      __syncthreads();
-      for (uint32_t i = threadIdx.x; i < count; i += kThreads) {
-        const uint32_t key = cl[i].key;
-        if (key >= lo && ((key - lo) >> width_shift) == 0u) atomicAdd(&s_hist[(key - lo) >> ns], 1u);
-      }
-      __syncthreads();
-      const BinHit hit = find_rank_from_top(s_hist, bins, r, s_part, s_out);
-      r -= hit.higher;
-      lo += hit.bin << ns;
-      width_shift = ns;
-    }
-    theta = lo;
-    // set the bits of the candidates at or above theta
-    uint32_t kept = 0;
-    for (uint32_t i = threadIdx.x; i < count; i += kThreads) {
-      const Candidate c = cl[i];
-      if (c.key >= theta) {
-        atomicOr(&td.mask[c.idx >> 5], 1u << (c.idx & 31u));
-        ++kept;
-      }
-    }
-    kept = wave_sum(kept);
-    __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = kept;
-    __syncthreads();
-    nnz = ls.above + s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  __shared__ uint32_t s_counts[kCandLists + 1];
+  if (threadIdx.x <= kCandLists) {
+    const uint32_t c = *cand_counter(counters, l, threadIdx.x);
+    s_counts[threadIdx.x] = min(c, threadIdx.x < kCandLists ? td.sub_cap : td.cand_cap);
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    ls.theta_key = theta;
-    ls.theta = u2f(theta);
-    ls.nnz = nnz;
-    ls.lambda = u2f(ls.acc_maxkey);
-    ls.curv_nonfinite = ls.acc_nonfinite;
-    ls.probes_seen = ls.probes_seen + 1;
-    // window of the next probed step: 2048 bins of 512 keys centred on this theta
-    const uint32_t p = theta >> kPredShift;
-    const uint32_t lo_bin = p > (uint32_t)(kHistBins / 2) ? p - kHistBins / 2 : 0u;
-    ls.mode = kSelHist;
-    ls.win_lo = lo_bin << kPredShift;
-    ls.win_shift = kPredShift;
-    ls.win_bins = kHistBins;
-    ls.predicted = 1;
-    ls.passes = 0;
-    ls.above = 0;
-    ls.k_rem = 0;
-    ls.sel_count = 0;
-    ls.acc_above = 0;
-    ls.acc_zeros = 0;
-    ls.acc_maxkey = 0;
-    ls.acc_nonfinite = 0;
-    ls.cand_count = 0;
+  const uint32_t mode = ls.mode;
+  const uint32_t above = ls.above;
+  const uint32_t rng_lo = ls.rng_lo, rng_hi = ls.rng_hi;
+  uint32_t theta = ls.theta_key;
+  uint32_t nnz = above + ls.sel_count;
+  if (mode == kSelExact && theta == 0u) nnz = ls.nonzero;
+  if (mode == kSelCand) {
+    uint32_t lo = rng_lo;
+    uint32_t width_shift = 31u - (uint32_t)__clz(rng_hi - rng_lo);  // range width is a power of two
+    uint32_t r = ls.k_rem - above;
+    // number of listed keys inside the range (the lists may also hold band keys outside it)
+    uint32_t inside = 0;
+    for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
+      inside += (c.key >= rng_lo && c.key < rng_hi) ? 1u : 0u;
+    });
+    inside = finish_block_sum(inside, s_red);
+    if (r > inside) {
+      theta = 0;  // fewer non-zero keys than k (small tensors only): keep every non-zero entry
+    } else {
+      while (width_shift > 0) {
+        const uint32_t ns = width_shift > (uint32_t)kHistBits ? width_shift - kHistBits : 0u;
+        const uint32_t bins = 1u << (width_shift - ns);
+        for (uint32_t b = threadIdx.x; b < bins; b += kFinishThreads) s_hist[b] = 0;
+        __syncthreads();
+        for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
+          if (c.key >= lo && ((c.key - lo) >> width_shift) == 0u) atomicAdd(&s_hist[(c.key - lo) >> ns], 1u);
+        });
+        __syncthreads();
+        const BinHit hit = find_rank_from_top<kFinishThreads>(s_hist, bins, r, s_part, s_out);
+        r -= hit.higher;
+        lo += hit.bin << ns;
+        width_shift = ns;
+      }
+      theta = lo;
+    }
   }
+  // Listed keys had their bits left clear: set those at or above theta.  Keys above the range
+  // are already counted in `above`.
+  if (mode == kSelCand || ls.mask_done) {
+    uint32_t kept = 0;
+    for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
+      if (c.key >= theta) {
+        atomicOr(&td.mask[c.idx >> 5], 1u << (c.idx & 31u));
+        kept += (c.key >= rng_lo && c.key < rng_hi) ? 1u : 0u;
+      }
+    });
+    kept = finish_block_sum(kept, s_red);
+    if (mode == kSelCand) nnz = above + kept;
+  }
+  __syncthreads();
+  reset_cand_counters(counters, l);
+  if (threadIdx.x != 0) return;
+  // ---- publish ----
+  const uint32_t prev = ls.theta_key_last;
+  const uint32_t have = ls.n_theta;
+  ls.theta_key = theta;
+  ls.theta = u2f(theta);
+  ls.nnz = nnz;
+  ls.sel_passes = ls.passes - 1 + (ls.mask_done ? 0u : 1u);  // passes over h beyond the EMA pass
+  ls.probes_seen = ls.probes_seen + 1;
+  // ---- plan the next probed step ----
+  // error of this step's prediction (or, without one, the step-to-step change)
+  uint32_t err;
+  if (ls.predicted) err = abs_diff(theta, ls.pred_center);
+  else if (have >= 1) err = abs_diff(theta, prev);
+  else err = kUnknownPredErr;  // nothing known yet: about 1 % in value
+  if (ls.window_missed) err = max(err, kUnknownPredErr);
+  const uint32_t e = max(max(err, ls.pred_err), 16u);
+  ls.pred_err = err;
+  ls.theta_key_last = theta;
+  ls.n_theta = have < 2 ? have + 1 : 2;
+  // centre: linear extrapolation in key space from the last two thresholds
+  int64_t centre = (int64_t)theta;
+  if (have >= 1) centre += (int64_t)theta - (int64_t)prev;
+  if (centre < 0) centre = 0;
+  if (centre > 0x7f7fffff) centre = 0x7f7fffff;
+  // bins: the half window (1024 bins) spans 32 e
+  uint32_t s = kMinPredShift;
+  while (s < kFullShift && ((uint64_t)1024 << s) < (uint64_t)32 * e) ++s;
+  const uint32_t cbin = (uint32_t)centre >> s;
+  const uint32_t lo_bin = cbin > (uint32_t)(kHistBins / 2) ? cbin - kHistBins / 2 : 0u;
+  // band: 4 e on either side, whole bins, inside the window
+  uint32_t hb = (uint32_t)(((uint64_t)4 * e + ((uint64_t)1 << s) - 1) >> s);
+  if (hb < 1) hb = 1;
+  if (hb > 512) hb = 512;
+  const uint32_t band_lo_bin = cbin > hb ? cbin - hb : 0u;
+  const uint32_t band_lo = max(band_lo_bin, lo_bin) << s;
+  const uint32_t band_hi = (cbin + hb + 1) << s;
+  // expected number of keys inside the band, from the key density around this step's threshold;
+  // listing them only pays when they fit the lists with room to spare
+  const uint64_t expect = ((uint64_t)(band_hi - band_lo) * ls.dens_count) >> ls.dens_shift;
+  ls.mode = kSelHist;
+  ls.win_lo = lo_bin << s;
+  ls.win_shift = s;
+  ls.win_bins = kHistBins;
+  ls.band_lo = band_lo;
+  ls.band_hi = band_hi;
+  ls.use_band = expect <= (uint64_t)(td.cand_cap - td.cand_cap / 4) ? 1u : 0u;
+  ls.pred_center = (uint32_t)centre;
+  ls.predicted = 1;
+  ls.window_missed = 0;
+  ls.mask_done = 0;
+  ls.passes = 0;
+  ls.above = 0;
+  ls.k_rem = 0;
+  ls.sel_count = 0;
+  ls.dens_count = 0;
+  ls.dens_shift = 0;
+  ls.acc_above = 0;
+  ls.acc_zeros = 0;
+  ls.acc_maxkey = 0;
+  ls.acc_nonfinite = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -702,7 +939,13 @@ __global__ __launch_bounds__(kThreads) void k_assign(const TensorDesc* __restric
     ls.var = (float)var;
     if (applied == 1) ls.v = (float)var;
     else ls.v = (float)((double)hp.beta_var * (double)ls.v + (1.0 - (double)hp.beta_var) * var);
-    if (!td.has_probe) ls.curv_nonfinite = 0;
+    // lambda_l = largest |h_i| (always inside the mask); accumulated by the EMA kernel of this step
+    if (td.has_probe) {
+      ls.lambda = u2f(ls.acc_maxkey);
+      ls.curv_nonfinite = ls.acc_nonfinite;
+    } else {
+      ls.curv_nonfinite = 0;
+    }
     const int prev = ls.code;
     ls.prev_code = prev;
     int code = prev;
@@ -792,68 +1035,75 @@ __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base,
   }
 }
 
-// Any combination of gradient / old / new precision, decided at run time (uniform per workgroup).
-template <bool MOM>
-__device__ __noinline__ void update_chunk_rt(const TensorDesc& td, int gd, int pd, int nd, int64_t base,
-                                             float inv_scale, float wd, float mu, float neg_eta, bool barrier) {
-  const int tid = threadIdx.x;
+template <int GD, int PD, int ND>
+__device__ __forceinline__ void update_dispatch2(const TensorDesc& td, int64_t base, float inv_scale, float wd,
+                                                 float mu, float neg_eta, bool barrier) {
   const bool full = base + kChunk <= td.numel;
-  float g[kRows][4], th[kRows][4], m[kRows][4];
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
-    load4_rt(gd, td.grad, idx, td.numel, full, g[r]);
-    load4_rt(pd, td.param, idx, td.numel, full, th[r]);
-    if (MOM) load4_rt(kFP32, td.mom, idx, td.numel, full, m[r]);
-  }
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float gt = g[r][i] * inv_scale;
-      const float d = fmaf(wd, th[r][i], gt);
-      const float mm = MOM ? fmaf(mu, m[r][i], d) : d;
-      m[r][i] = mm;
-      th[r][i] = fmaf(neg_eta, mm, th[r][i]);
-    }
-  }
-  if (barrier) __syncthreads();
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
-    store4_rt(nd, td.param, idx, td.numel, full, th[r]);
-    if (MOM) store4_rt(kFP32, td.mom, idx, td.numel, full, m[r]);
+  const bool mom = td.mom != nullptr;
+  if (full) {
+    if (mom) update_chunk<GD, PD, ND, true, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
+    else update_chunk<GD, PD, ND, true, false>(td, base, inv_scale, wd, mu, neg_eta, barrier);
+  } else {
+    if (mom) update_chunk<GD, PD, ND, false, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
+    else update_chunk<GD, PD, ND, false, false>(td, base, inv_scale, wd, mu, neg_eta, barrier);
   }
 }
 
+template <int GD, int PD>
+__device__ __forceinline__ void update_dispatch1(int nd, const TensorDesc& td, int64_t base, float inv_scale,
+                                                 float wd, float mu, float neg_eta, bool barrier) {
+  switch (nd) {
+    case kFP32: update_dispatch2<GD, PD, kFP32>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kBF16: update_dispatch2<GD, PD, kBF16>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    default: update_dispatch2<GD, PD, kFP16>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+  }
+}
+
+template <int GD>
+__device__ __forceinline__ void update_dispatch0(int pd, int nd, const TensorDesc& td, int64_t base,
+                                                 float inv_scale, float wd, float mu, float neg_eta, bool barrier) {
+  switch (pd) {
+    case kFP32: update_dispatch1<GD, kFP32>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kBF16: update_dispatch1<GD, kBF16>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    default: update_dispatch1<GD, kFP16>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+  }
+}
+
+// Gradient, old and new precision are uniform over a workgroup: branch once per chunk into a body
+// specialised for the combination.
 __device__ __forceinline__ void update_any(const TensorDesc& td, int pd, int nd, int64_t base, float inv_scale,
                                            float wd, float mu, float neg_eta, bool barrier) {
-  const bool full = base + kChunk <= td.numel;
-  const bool mom = td.mom != nullptr;
-  // the streaming case gets a fully specialised body: fp32 gradients, fp32 parameters, whole chunk
-  if (full && mom && td.grad_dtype == kFP32 && pd == kFP32 && nd == kFP32) {
-    update_chunk<kFP32, kFP32, kFP32, true, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
-  } else if (full && mom && td.grad_dtype == kFP32 && pd == kBF16 && nd == kBF16) {
-    update_chunk<kFP32, kBF16, kBF16, true, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
-  } else if (mom) {
-    update_chunk_rt<true>(td, td.grad_dtype, pd, nd, base, inv_scale, wd, mu, neg_eta, barrier);
-  } else {
-    update_chunk_rt<false>(td, td.grad_dtype, pd, nd, base, inv_scale, wd, mu, neg_eta, barrier);
+  switch (td.grad_dtype) {
+    case kFP32: update_dispatch0<kFP32>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kBF16: update_dispatch0<kBF16>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    default: update_dispatch0<kFP16>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
   }
 }
 
 // Tensors whose storage size does not change: element i is read and written at the same address
-// by the same lane, so the update is in place.  One workgroup per chunk.
+// by the same lane, so the update is in place.  One workgroup per chunk.  The same workgroup then
+// runs the fallback mask pass of its chunk when the tensor's mask was not settled by the EMA
+// kernel (nothing in the update depends on the mask, and a separate launch would cost a full
+// grid of idle workgroups on every step that needs no fallback).
 __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restrict__ tds,
-                                                     const ChunkRef* __restrict__ chunks, const LayerDev* layers,
-                                                     const GlobalDev* glob, StepScalars sc, float wd, float mu) {
+                                                     const ChunkRef* __restrict__ chunks, LayerDev* layers,
+                                                     const GlobalDev* glob, Candidate* cands, uint32_t* counters,
+                                                     StepScalars sc, float wd, float mu) {
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
-  const LayerDev& ls = layers[cr.tensor];
+  LayerDev& ls = layers[cr.tensor];
   const int pd = ls.prev_code, nd = ls.code;
-  if (elem_size(pd) != elem_size(nd)) return;
   const TensorDesc td = tds[cr.tensor];
-  update_any(td, pd, nd, (int64_t)cr.index * kChunk, sc.inv_scale, wd, mu, -ls.eta, false);
+  const int64_t base = (int64_t)cr.index * kChunk;
+  if (elem_size(pd) == elem_size(nd)) update_any(td, pd, nd, base, sc.inv_scale, wd, mu, -ls.eta, false);
+  // kSelHist cannot remain after the last scan; never write a mask from a stale range
+  const uint32_t mode = ls.mode;
+  if (td.has_probe && !ls.mask_done && mode != kSelHist) {
+    if (base + kChunk <= td.numel)
+      mask_chunk<true>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
+    else
+      mask_chunk<false>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
+  }
 }
 
 // Tensors whose storage size changes (2 <-> 4 bytes per element) are rewritten in place in
@@ -920,7 +1170,7 @@ hipError_t launch_curv_ema_hist(const DeviceTables& t, const StepScalars& sc, fl
                                 hipStream_t s) {
   const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_curv_ema_hist, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks,
-                     t.layers, t.glob, t.hist, sc, beta_h, omb_h);
+                     t.layers, t.glob, t.hist, t.cands, t.cand_counters, sc, beta_h, omb_h);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -934,22 +1184,15 @@ hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStr
 }
 
 hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s) {
-  hipLaunchKernelGGL(k_select_scan, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.hist, sc,
-                     sparsity_ppm);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
-hipError_t launch_mask(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
-  hipLaunchKernelGGL(k_mask, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                     t.cands, sc);
+  hipLaunchKernelGGL(k_select_scan, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.hist,
+                     t.cand_counters, sc, sparsity_ppm);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
-  hipLaunchKernelGGL(k_select_finish, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.cands,
-                     sc);
+  hipLaunchKernelGGL(k_select_finish, dim3(t.n_tensors), dim3(kFinishThreads), 0, s, t.tensors, t.layers, t.glob,
+                     t.cands, t.cand_counters, sc);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -962,8 +1205,8 @@ hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyp
 }
 
 hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s) {
-  hipLaunchKernelGGL(k_update, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob, sc,
-                     wd, mu);
+  hipLaunchKernelGGL(k_update, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
+                     t.cands, t.cand_counters, sc, wd, mu);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

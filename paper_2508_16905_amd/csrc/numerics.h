@@ -1,8 +1,6 @@
 // Device-side number-format conversions and 4-element vector accessors (gfx950).
 //
-// Conversions are integer bit manipulation so that their result does not depend on the
-// wavefront's floating-point mode: IEEE round-to-nearest-even, overflow to infinity,
-// subnormals produced exactly, NaN kept quiet.
+// IEEE round-to-nearest-even, overflow to infinity, subnormals produced exactly, NaN kept NaN.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,49 +12,29 @@ enum : int { kFP16 = 0, kBF16 = 1, kFP32 = 2 };
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 
+// Conversions use the gfx950 conversion instructions through the language casts: v_cvt_f16_f32 /
+// v_cvt_pk_bf16_f32 round to nearest even (the mode HIP kernels run in), overflow to infinity
+// and produce subnormals exactly; v_cvt_f32_f16 and the 16-bit shift of bfloat16 are exact.
+// The result is checked against the CPU oracle for all 2^32 inputs by the GPU test suite.
+//
+// The fp32 value is pinned in a register before it is narrowed: otherwise the compiler may merge
+// the producing fused multiply-add with the conversion into one mixed-precision instruction that
+// rounds the exact product-sum once, straight to 16 bits, instead of first to fp32 and then to 16
+// bits as the update is defined.
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
-  uint32_t u = f2u(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return ((u >> 16) & 0x8000u) | 0x7fc0u;  // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);  // ties to even; carries into the exponent, up to infinity
-  return u >> 16;
+  asm volatile("" : "+v"(x));
+  const __bf16 b = (__bf16)x;
+  return (uint32_t)__builtin_bit_cast(unsigned short, b);
 }
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float x) {
-  const uint32_t u = f2u(x);
-  const uint32_t sign = (u >> 16) & 0x8000u;
-  const uint32_t a = u & 0x7fffffffu;
-  if (a > 0x7f800000u) return sign | 0x7e00u;   // NaN
-  if (a >= 0x477ff000u) return sign | 0x7c00u;  // |x| >= 65520 rounds to infinity
-  if (a < 0x38800000u) {                        // |x| < 2^-14: subnormal result, quantum 2^-24
-    if (a < 0x33000000u) return sign;           // |x| < 2^-25 rounds to zero
-    const uint32_t e = a >> 23;                 // 102 .. 112
-    const uint32_t m = (a & 0x007fffffu) | 0x00800000u;
-    const uint32_t shift = 126u - e;            // 14 .. 24
-    uint32_t q = m >> shift;
-    const uint32_t rem = m & ((1u << shift) - 1u);
-    const uint32_t half = 1u << (shift - 1u);
-    if (rem > half || (rem == half && (q & 1u))) ++q;
-    return sign | q;                            // q == 1024 is the smallest normal number
-  }
-  uint32_t h = (((a >> 23) - 112u) << 10) | ((a >> 13) & 0x3ffu);
-  const uint32_t rem = a & 0x1fffu;
-  if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;  // may carry into the exponent
-  return sign | h;
+  asm volatile("" : "+v"(x));
+  const _Float16 h = (_Float16)x;
+  return (uint32_t)__builtin_bit_cast(unsigned short, h);
 }
 
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
-  const uint32_t sign = (h & 0x8000u) << 16;
-  const uint32_t e = (h >> 10) & 31u;
-  const uint32_t m = h & 0x3ffu;
-  if (e == 0u) {
-    if (m == 0u) return u2f(sign);
-    // subnormal m * 2^-24: normalise with integer shifts
-    const uint32_t lz = __clz(m) - 21u;  // m has at most 10 bits; lz = shifts to reach bit 10
-    const uint32_t mm = (m << lz) & 0x3ffu;
-    return u2f(sign | ((113u - lz) << 23) | (mm << 13));
-  }
-  if (e == 31u) return u2f(sign | 0x7f800000u | (m << 13));
-  return u2f(sign | ((e + 112u) << 23) | (m << 13));
+  return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return u2f(b << 16); }
@@ -133,19 +111,6 @@ __device__ __forceinline__ void store4_guard(void* base, int64_t idx, int64_t n,
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (idx + i < n) store1<DT>(base, idx + i, v[i]);
-}
-
-// Runtime-dtype variants (the dtype is uniform over a workgroup, so the branch does not diverge).
-__device__ __forceinline__ void load4_rt(int dt, const void* base, int64_t idx, int64_t n, bool full, float out[4]) {
-  if (dt == kFP32) { if (full) load4<kFP32>(base, idx, out); else load4_guard<kFP32>(base, idx, n, 0.0f, out); }
-  else if (dt == kBF16) { if (full) load4<kBF16>(base, idx, out); else load4_guard<kBF16>(base, idx, n, 0.0f, out); }
-  else { if (full) load4<kFP16>(base, idx, out); else load4_guard<kFP16>(base, idx, n, 0.0f, out); }
-}
-
-__device__ __forceinline__ void store4_rt(int dt, void* base, int64_t idx, int64_t n, bool full, const float v[4]) {
-  if (dt == kFP32) { if (full) store4<kFP32>(base, idx, v); else store4_guard<kFP32>(base, idx, n, v); }
-  else if (dt == kBF16) { if (full) store4<kBF16>(base, idx, v); else store4_guard<kBF16>(base, idx, n, v); }
-  else { if (full) store4<kFP16>(base, idx, v); else store4_guard<kFP16>(base, idx, n, v); }
 }
 
 }  // namespace triaccel

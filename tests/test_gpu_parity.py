@@ -188,3 +188,30 @@ def test_large_variance_offset():
         sigma = wl.layer_consts(0)["sigma"]
         p.step([x + 1e4 * sigma for x in g], z, hz, label="offset gradients")
     p.close()
+
+
+def test_threshold_prediction_across_many_steps():
+    # long enough for the threshold prediction to go through all its regimes on large tensors:
+    # no prediction, wide window with fallback mask pass, narrow band resolved in the EMA pass
+    wl = get_workload("large_streaming", n_tensors=3, side=700)
+    Pair(wl).run(40).close()
+
+
+def test_harness_detects_a_mistake_planted_in_the_oracle():
+    # the comparison must fail when the oracle's state is perturbed (one mask bit, one parameter
+    # bit, one curvature value, one code): guards against a harness that compares nothing
+    wl = custom([5000, 33])
+    p = Pair(wl).run(2)
+    o = p.orc.tensors[0]
+    for mutate, undo in (
+        (lambda: o.mask.__setitem__(3, o.mask[3] ^ 1), lambda: o.mask.__setitem__(3, o.mask[3] ^ 1)),
+        (lambda: o.buf.__setitem__(40, o.buf[40] ^ 1), lambda: o.buf.__setitem__(40, o.buf[40] ^ 1)),
+        (lambda: o.curv.__setitem__(7, o.curv[7] * 2), lambda: o.curv.__setitem__(7, o.curv[7] / 2)),
+        (lambda: setattr(o, "nnz", o.nnz + 1), lambda: setattr(o, "nnz", o.nnz - 1)),
+    ):
+        mutate()
+        with pytest.raises(AssertionError):
+            p.compare("planted")
+        undo()
+    p.compare("restored")
+    p.close()

@@ -28,11 +28,11 @@ def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, m
     statistics read g; the EMA reads z, Hz, h and writes h; the mask pass re-reads h and writes one
     bit per element; the update reads g, the stored parameter and m, and writes the parameter and m."""
     size = lambda c: 4 if c == 2 else 2
-    b = dict(grad_stats=0, curv_ema_hist=0, mask_in_ema=0, mask_fallback=0, update=0, update_resize=0)
+    b = dict(grad_stats=0, curv_ema=0, mask_in_ema=0, mask_fallback=0, update=0, update_resize=0)
     for n, pc, c, extra in zip(numel, prev_codes, codes, sel_passes):
         b["grad_stats"] += n * grad_size
         if probed:
-            b["curv_ema_hist"] += n * 16
+            b["curv_ema"] += n * 16
             # the exact threshold needs |h| once more after the pass that creates it; that re-read is
             # part of the method's traffic whether or not the prediction lets the kernels skip it
             b["mask_fallback" if extra else "mask_in_ema"] += n * 4 + n / 8.0
@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tensors", type=int, default=0, help="use only the first N tensors of the workload (tuning runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -69,6 +70,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = get_workload(args.workload)
+    if args.tensors:
+        wl.tensors = wl.tensors[: args.tensors]
     hyper = dict(wl.hyper)
     if args.all_fp32:
         hyper.update(tau_low=0.0, tau_high=0.0)
@@ -128,7 +131,7 @@ def main():
     alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, True, hyper["momentum"] != 0.0)
     total_bytes = sum(alg.values())
     # bytes each kernel stage actually has to move in the last timed step
-    moved = {"grad_stats": alg["grad_stats"], "curv_ema_hist": alg["curv_ema_hist"] + alg["mask_in_ema"] / 33.0,
+    moved = {"grad_stats": alg["grad_stats"], "curv_ema": alg["curv_ema"] + alg["mask_in_ema"] / 33.0,
              "update": alg["update"] + alg["mask_fallback"], "update_resize": alg["update_resize"]}
     stages = {}
     for name in ta.STAGE_NAMES:

@@ -12,11 +12,12 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtriaccel.so")
+# TRIACCEL_LIBRARY overrides the in-tree build (e.g. to try a differently tuned build of the library)
+LIB_PATH = os.environ.get("TRIACCEL_LIBRARY") or os.path.join(_HERE, "libtriaccel.so")
 
 FP16, BF16, FP32 = 0, 1, 2
 N_STAGES = 7
-STAGE_NAMES = ("grad_stats", "curv_ema_hist", "select_refine", "assign", "update", "update_resize", "select_finish")
+STAGE_NAMES = ("grad_stats", "curv_ema", "select_refine", "assign", "update", "update_resize", "select_finish")
 
 
 class Config(C.Structure):

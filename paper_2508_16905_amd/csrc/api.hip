@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -222,6 +223,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   if ((rc = dev_alloc(c, &T.tensors, (size_t)n))) return fail(rc);
   if ((rc = dev_alloc(c, &T.chunks, chunks.size()))) return fail(rc);
   if ((rc = dev_alloc(c, &T.partials, chunks.size()))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.ema_partials, chunks.size()))) return fail(rc);
   if ((rc = dev_alloc(c, &T.layers, (size_t)n))) return fail(rc);
   if ((rc = dev_alloc(c, &T.glob, 1))) return fail(rc);
   if ((rc = dev_alloc(c, &T.hist, (size_t)n * kHistBins))) return fail(rc);
@@ -319,15 +321,16 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   TA_HIP(launch_grad_stats(T, sc, s));
   if (prof) TA_HIP(hipEventRecord(ev[1], s));
   if (any_probe) {
-    TA_HIP(launch_curv_ema_hist(T, sc, beta_h, omb_h, s));
-    TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
+    TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, s));
+    TA_HIP(launch_select_begin(T, sc, h->cfg.sparsity_ppm, s));
   }
   if (prof) TA_HIP(hipEventRecord(ev[2], s));
   if (any_probe) {
-    // at most three refinement rounds are ever needed (11 + 11 + 9 key bits after a missed prediction)
-    for (int round = 0; round < 3; ++round) {
+    // fallback radix select; at most four rounds are ever needed: a predicted window that misses,
+    // then 11 + 11 + 9 key bits.  Idle (a few workgroups that exit) when the prediction held.
+    for (int round = 0; round < 4; ++round) {
       TA_HIP(launch_hist_pass(T, sc, s));
-      TA_HIP(launch_select_scan(T, sc, h->cfg.sparsity_ppm, s));
+      TA_HIP(launch_select_scan(T, sc, s));
     }
   }
   if (prof) TA_HIP(hipEventRecord(ev[3], s));

@@ -93,7 +93,7 @@ struct LayerDev {
   uint32_t mask_done;      // the mask needs no separate pass this step
   uint32_t window_missed;  // the predicted window did not contain theta this step
   uint32_t mode;           // SelMode
-  uint32_t win_lo, win_shift, win_bins;  // histogram window: bin = (key - win_lo) >> win_shift
+  uint32_t win_lo, win_shift, win_bins;  // histogram window (fallback passes): bin = (key - win_lo) >> win_shift
   uint32_t predicted;      // the window was centred on the previous theta
   uint32_t passes;         // scans done in this step (0 = the first histogram has not been scanned yet)
   uint32_t k_rem;          // rank still to resolve inside [rng_lo, rng_hi) (1 = largest)
@@ -101,7 +101,8 @@ struct LayerDev {
   uint32_t rng_lo, rng_hi; // candidate range (kSelCand)
   uint32_t sel_count;      // keys equal to theta (kSelExact) or inside the range (kSelCand)
   uint32_t nonzero;        // number of non-zero keys
-  uint32_t dens_count, dens_shift;  // key density near theta: dens_count keys per 2^dens_shift keys
+  uint32_t dens_count, dens_width;  // key density near theta: dens_count keys per dens_width keys
+  uint32_t count_above;    // the next histogram pass must count the keys above its window
   // accumulators filled by atomics during a step and cleared by the kernel that consumes them
   uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite;
 };
@@ -126,6 +127,13 @@ struct ChunkRef {
 struct Candidate {
   uint32_t idx;
   uint32_t key;
+};
+
+struct EmaPartial {
+  uint32_t above;      // keys at or above the band
+  uint32_t zeros;      // zero keys
+  uint32_t maxkey;     // largest key
+  uint32_t nonfinite;  // a probe sample of the chunk was non-finite
 };
 
 struct StatPartial {

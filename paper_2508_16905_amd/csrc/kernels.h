@@ -11,6 +11,7 @@ struct DeviceTables {
   TensorDesc* tensors;
   ChunkRef* chunks;
   StatPartial* partials;
+  EmaPartial* ema_partials;  // one record per chunk, written by the EMA kernel
   LayerDev* layers;
   GlobalDev* glob;
   uint32_t* hist;        // n_tensors x kHistBins
@@ -25,9 +26,10 @@ struct DeviceTables {
 };
 
 hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
-hipError_t launch_curv_ema_hist(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
+hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
+hipError_t launch_select_begin(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s);
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
-hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s);
+hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
 hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);

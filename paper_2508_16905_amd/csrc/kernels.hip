@@ -159,20 +159,18 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
 }
 
 // ---------------------------------------------------------------------------------------------
-// Threshold selection (exact k-th largest |h_i| per tensor) -- radix select on the 31-bit
-// magnitude keys, organised so that a probed step normally needs NO pass over h beyond the one
-// that creates it:
+// Threshold selection (exact k-th largest |h_i| per tensor) on the 31-bit magnitude keys,
+// organised so that a probed step normally needs NO pass over h beyond the one that creates it:
 //
-//   * The EMA kernel histograms the new keys inside a WINDOW of 2048 bins placed around the
-//     threshold predicted from the two previous steps, counts the keys above the window, writes a
-//     provisional mask (bit = key above a narrow BAND around the prediction) and lists the keys
-//     inside the band as candidates.
-//   * A scan per tensor finds the bin holding the k-th largest key.  If that bin lies inside the
-//     band, the listed candidates resolve theta exactly and only their mask bits are patched.
-//   * Otherwise (no prediction yet, prediction off, too many candidates) the tensor falls back
-//     to further histogram passes over h and a separate mask pass.
-//   * Tensors with at most kCandCap elements skip the histogram: all their non-zero keys are
-//     listed and selected from the list.
+//   * From the thresholds of the two previous probed steps the library predicts this step's
+//     threshold and a BAND around it (a few times the error the last predictions made).
+//   * The EMA kernel writes a provisional mask (bit = key at or above the band), lists the keys
+//     inside the band, and counts the keys above it.
+//   * If the k-th largest key falls inside the band (count above < k <= count above + listed),
+//     the listed keys resolve theta exactly and only their mask bits are patched.
+//   * Otherwise (no prediction yet, prediction off, too many keys to list) the tensor falls
+//     back to a radix select by histogram passes over h and a separate mask pass.
+//   * Tensors with at most kCandCap elements list all their non-zero keys and select from the list.
 // ---------------------------------------------------------------------------------------------
 struct Window {
   uint32_t lo, shift, bins;
@@ -191,11 +189,11 @@ __device__ __forceinline__ void flush_hist(uint32_t* s_hist, uint32_t bins, uint
   __syncthreads();
 }
 
-// Eight consecutive lanes hold the 32 elements of one mask word: combine their 4-bit nibbles.
 // Data-parallel-primitive moves inside the wavefront (no LDS traffic): swap neighbours in a quad,
 // swap the quad's halves, then mirror the 8-lane half row (lane i reads lane 7 - i; after the first
 // two steps all four lanes of a quad agree, so the mirror brings in the other quad's value).
 #define TA_DPP_OR(v, ctrl) ((v) | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), 0xF, 0xF, true))
+// Eight consecutive lanes hold the 32 elements of one mask word: combine their 4-bit nibbles.
 __device__ __forceinline__ uint32_t gather_mask_word(uint32_t nib, int lane) {
   uint32_t v = nib << (4 * (lane & 7));
   v = TA_DPP_OR(v, 0xB1);   // quad_perm [1, 0, 3, 2]
@@ -221,8 +219,8 @@ __device__ __forceinline__ void store_mask_words(const TensorDesc& td, int64_t b
 // Candidate storage.  Each tensor owns kCandLists sub-lists of sub_cap entries plus one overflow
 // list of cand_cap entries, each with its own counter in its own 128-byte line: appends from
 // different chunks and wavefronts go to different counters, because atomics on one hot address
-// serialise.  A batch that does not fit its sub-list spills into the overflow
-// list, so nothing is lost as long as the tensor lists at most cand_cap keys in total.
+// serialise.  A batch that does not fit its sub-list spills into the overflow list, so nothing
+// is lost as long as the tensor lists at most cand_cap keys in total.
 __device__ __forceinline__ uint32_t* cand_counter(uint32_t* counters, uint32_t tensor, uint32_t list) {
   return counters + ((size_t)tensor * (kCandLists + 1) + list) * kCandCounterStride;
 }
@@ -291,30 +289,19 @@ __device__ __forceinline__ void for_each_candidate(const TensorDesc& td, const C
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 2: curvature EMA (diagonal Hutchinson signal of Sec. 3.2) fused with the first pass of
-// the threshold selection.  Persistent workgroups, each owning a contiguous range of chunks so
-// that the LDS histogram is flushed once per (workgroup, tensor).
+// Stage 2: curvature EMA (diagonal Hutchinson signal of Sec. 3.2), one workgroup per chunk.
 // Per element, fp32:  u = (z * hz) * inv_scale;  h = u on the tensor's first probe, else
 // h = fma(beta_h, h, (1 - beta_h) * u);  a non-finite u leaves h unchanged.
+// The same pass writes the provisional mask, lists the keys of the band and leaves one small
+// record per chunk (keys above the band, zero keys, largest key, non-finite flag); no atomics
+// except the candidate appends.
 // ---------------------------------------------------------------------------------------------
-struct EmaPlan {
-  Window w;
-  uint32_t band_lo, band_hi;
-  bool first;      // first probe of the tensor: h = u
-  bool hist;       // histogram the keys inside the window
-  bool band;       // write the provisional mask and list the keys inside [band_lo, band_hi)
-  bool list_all;   // small tensor: list every non-zero key, provisional mask all zero
-};
-
-struct EmaAcc {
-  uint32_t above, zeros, maxkey, nonfin;
-};
-
 template <bool FULL>
 __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, float inv_scale, float beta_h,
-                                          float omb_h, const EmaPlan& pl, uint32_t* s_hist, EmaAcc& acc,
-                                          uint32_t chunk_index, uint32_t tensor, Candidate* cands,
-                                          uint32_t* counters) {
+                                          float omb_h, bool first, bool band, bool list_all, uint32_t band_lo,
+                                          uint32_t band_hi, uint32_t chunk_index, uint32_t tensor, Candidate* cands,
+                                          uint32_t* counters, uint32_t& above_zeros, uint32_t& maxkey,
+                                          uint32_t& nonfin) {
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   float z[kRows][4], hz[kRows][4], h[kRows][4];
@@ -344,8 +331,8 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
       float hn = h[r][i];
       const bool valid = FULL || idx + i < td.numel;
       if ((f2u(u) & 0x7f800000u) == 0x7f800000u) {
-        if (valid) acc.nonfin = 1u;
-      } else if (pl.first) {
+        if (valid) nonfin = 1u;
+      } else if (first) {
         hn = u;
       } else {
         const float p = omb_h * u;
@@ -354,99 +341,85 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
       h[r][i] = hn;
       if (valid) {
         const uint32_t key = f2u(hn) & 0x7fffffffu;
-        acc.maxkey = max(acc.maxkey, key);
+        maxkey = max(maxkey, key);
         if (key == 0u) {
-          ++acc.zeros;
-        } else {
-          if (pl.hist && key >= pl.w.lo) {
-            const uint32_t bin = (key - pl.w.lo) >> pl.w.shift;
-            if (bin < pl.w.bins) atomicAdd(&s_hist[bin], 1u);
-            else ++acc.above;
-          }
-          if (pl.list_all) {
+          above_zeros += 1u << 16;  // zero keys in the high half, keys above the band in the low half
+        } else if (list_all) {
+          cflags |= 1u << (r * 4 + i);
+        } else if (band) {
+          if (key >= band_hi) {
+            nib |= 1u << i;
+            above_zeros += 1u;
+          } else if (key >= band_lo) {
             cflags |= 1u << (r * 4 + i);
-          } else if (pl.band) {
-            if (key >= pl.band_hi) nib |= 1u << i;
-            else if (key >= pl.band_lo) cflags |= 1u << (r * 4 + i);
           }
         }
       }
     }
     if (FULL) store4<kFP32>(td.curv, idx, h[r]);
     else store4_guard<kFP32>(td.curv, idx, td.numel, h[r]);
-    if (pl.band || pl.list_all) word[r] = gather_mask_word(nib, lane);
+    if (band || list_all) word[r] = gather_mask_word(nib, lane);
   }
-  if (pl.band || pl.list_all) {
+  if (band || list_all) {
     store_mask_words<FULL>(td, base, word);
     append_candidates(cflags, h, base, chunk_index, tensor, td, cands, counters);
   }
 }
 
-__global__ __launch_bounds__(kThreads) void k_curv_ema_hist(const TensorDesc* __restrict__ tds,
-                                                            const ChunkRef* __restrict__ chunks,
-                                                            uint32_t total_chunks, LayerDev* layers,
-                                                            const GlobalDev* glob, uint32_t* hist, Candidate* cands,
-                                                            uint32_t* counters, StepScalars sc, float beta_h,
-                                                            float omb_h) {
+__global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restrict__ tds,
+                                                       const ChunkRef* __restrict__ chunks, const LayerDev* layers,
+                                                       const GlobalDev* glob, EmaPartial* __restrict__ ema_partials,
+                                                       Candidate* cands, uint32_t* counters, StepScalars sc,
+                                                       float beta_h, float omb_h) {
   if (step_skipped(glob, sc.step_id)) return;
-  __shared__ uint32_t s_hist[kHistBins];
-  for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+  const ChunkRef cr = chunks[blockIdx.x];
+  const TensorDesc td = tds[cr.tensor];
+  if (!td.has_probe) return;
+  const LayerDev& ls = layers[cr.tensor];
+  const bool first = ls.probes_seen == 0;
+  const bool list_all = td.list_all != 0;
+  const bool band = !list_all && ls.use_band != 0;
+  const uint32_t band_lo = ls.band_lo, band_hi = ls.band_hi;
+  const int64_t base = (int64_t)cr.index * kChunk;
+  uint32_t above_zeros = 0, maxkey = 0, nonfin = 0;
+  if (base + kChunk <= td.numel)
+    ema_chunk<true>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index,
+                    cr.tensor, cands, counters, above_zeros, maxkey, nonfin);
+  else
+    ema_chunk<false>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index,
+                     cr.tensor, cands, counters, above_zeros, maxkey, nonfin);
+  // per-chunk record: fixed-order reduction over lanes and wavefronts, one plain store
+  above_zeros = wave_sum(above_zeros);  // at most 4096 in either half: no carry between the halves
+  maxkey = wave_max(maxkey);
+  const uint32_t anynf = __any(nonfin != 0u) ? 1u : 0u;
+  __shared__ uint32_t s_red[3][kThreads / kWave];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  if (lane == 0) {
+    s_red[0][wave] = above_zeros;
+    s_red[1][wave] = maxkey;
+    s_red[2][wave] = anynf;
+  }
   __syncthreads();
-  const uint32_t per = (total_chunks + gridDim.x - 1) / gridDim.x;
-  const uint32_t c0 = blockIdx.x * per;
-  const uint32_t c1 = min(c0 + per, total_chunks);
-  int cur = -1;
-  bool active = false;
-  EmaPlan pl{};
-  EmaAcc acc{0, 0, 0, 0};
-  TensorDesc td;
-  for (uint32_t c = c0; c <= c1; ++c) {
-    const bool end = (c == c1);
-    const int t = end ? -2 : (int)chunks[c].tensor;
-    if (t != cur) {
-      if (cur >= 0 && active) {
-        if (pl.hist) flush_hist(s_hist, pl.w.bins, hist + (size_t)cur * kHistBins);
-        const uint32_t above = wave_sum(acc.above), zeros = wave_sum(acc.zeros);
-        const uint32_t maxkey = wave_max(acc.maxkey), nonfin = wave_or(acc.nonfin);
-        if ((threadIdx.x & (kWave - 1)) == 0) {
-          LayerDev& ls = layers[cur];
-          if (above) atomicAdd(&ls.acc_above, above);
-          if (zeros) atomicAdd(&ls.acc_zeros, zeros);
-          if (maxkey) atomicMax(&ls.acc_maxkey, maxkey);
-          if (nonfin) atomicOr(&ls.acc_nonfinite, 1u);
-        }
-      }
-      if (end) break;
-      cur = t;
-      td = tds[t];
-      active = td.has_probe != 0;
-      const LayerDev& ls = layers[t];
-      pl.w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
-      pl.band_lo = ls.band_lo;
-      pl.band_hi = ls.band_hi;
-      pl.first = ls.probes_seen == 0;
-      pl.list_all = td.list_all != 0;
-      pl.hist = !pl.list_all;
-      pl.band = !pl.list_all && ls.use_band != 0;
-      acc = EmaAcc{0, 0, 0, 0};
+  if (threadIdx.x == 0) {
+    uint32_t az = 0, mk = 0, nf = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / kWave; ++w) {
+      az += s_red[0][w];
+      mk = max(mk, s_red[1][w]);
+      nf |= s_red[2][w];
     }
-    if (!active) continue;
-    const int64_t base = (int64_t)chunks[c].index * kChunk;
-    if (base + kChunk <= td.numel)
-      ema_chunk<true>(td, base, sc.inv_scale, beta_h, omb_h, pl, s_hist, acc, chunks[c].index, (uint32_t)cur, cands,
-                      counters);
-    else
-      ema_chunk<false>(td, base, sc.inv_scale, beta_h, omb_h, pl, s_hist, acc, chunks[c].index, (uint32_t)cur, cands,
-                       counters);
+    ema_partials[blockIdx.x] = EmaPartial{az & 0xffffu, az >> 16, mk, nf};
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fallback: one more histogram pass over |h| for tensors whose window still holds too many keys
-// to list (mode kSelHist after a scan).  Same chunk ownership as stage 2; reads h only.
+// Fallback: histogram pass over |h| for tensors whose threshold is not yet confined to a range
+// whose keys can be listed (mode kSelHist).  Persistent workgroups, each owning a contiguous
+// range of chunks so that the LDS histogram is flushed once per (workgroup, tensor); reads h only.
 // ---------------------------------------------------------------------------------------------
 template <bool FULL>
-__device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, const Window& w, uint32_t* s_hist) {
+__device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, const Window& w, uint32_t* s_hist,
+                                           bool count_above, uint32_t& above) {
   const int tid = threadIdx.x;
   float h[kRows][4];
 #pragma unroll
@@ -463,6 +436,7 @@ __device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, c
       if (key != 0u && key >= w.lo) {
         const uint32_t bin = (key - w.lo) >> w.shift;
         if (bin < w.bins) atomicAdd(&s_hist[bin], 1u);
+        else if (count_above) ++above;
       }
     }
   }
@@ -470,31 +444,48 @@ __device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, c
 
 __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
                                                         const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
-                                                        const LayerDev* layers, const GlobalDev* glob,
-                                                        uint32_t* hist, StepScalars sc) {
+                                                        LayerDev* layers, const GlobalDev* glob, uint32_t* hist,
+                                                        StepScalars sc) {
   if (step_skipped(glob, sc.step_id)) return;
-  __shared__ uint32_t s_hist[kHistBins];
-  for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
-  __syncthreads();
   const uint32_t per = (total_chunks + gridDim.x - 1) / gridDim.x;
   const uint32_t c0 = blockIdx.x * per;
   const uint32_t c1 = min(c0 + per, total_chunks);
+  // nothing to do for this workgroup (the usual case: the prediction held): leave at once
+  bool any_active = false;
+  for (uint32_t c = c0; c < c1;) {
+    const uint32_t t = chunks[c].tensor;
+    const LayerDev& ls = layers[t];
+    any_active = any_active || (tds[t].has_probe != 0 && ls.mode == kSelHist && ls.passes > 0);
+    c = tds[t].first_chunk + tds[t].n_chunks;
+  }
+  if (!any_active) return;
+  __shared__ uint32_t s_hist[kHistBins];
+  for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+  __syncthreads();
   int cur = -1;
   bool active = false;
   Window w{0, 0, 0};
   TensorDesc td;
+  bool count_above = false;  // the number of keys above the window is not known yet (predicted window)
+  uint32_t above = 0;
   uint32_t c = c0;
   while (c <= c1) {
     const bool end = (c == c1);
     const int t = end ? -2 : (int)chunks[c].tensor;
     if (t != cur) {
-      if (cur >= 0 && active) flush_hist(s_hist, w.bins, hist + (size_t)cur * kHistBins);
+      if (cur >= 0 && active) {
+        flush_hist(s_hist, w.bins, hist + (size_t)cur * kHistBins);
+        above = wave_sum(above);
+        if ((threadIdx.x & (kWave - 1)) == 0 && above) atomicAdd(&layers[cur].acc_above, above);
+      }
       if (end) break;
       cur = t;
       td = tds[t];
       const LayerDev& ls = layers[t];
       active = td.has_probe != 0 && ls.mode == kSelHist && ls.passes > 0;
       w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
+      count_above = ls.count_above != 0;
+      above = 0;
       if (!active) {
         // jump over the rest of this tensor's chunks owned by this workgroup
         c = min(td.first_chunk + td.n_chunks, c1);
@@ -502,8 +493,8 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
       }
     }
     const int64_t base = (int64_t)chunks[c].index * kChunk;
-    if (base + kChunk <= td.numel) hist_chunk<true>(td, base, w, s_hist);
-    else hist_chunk<false>(td, base, w, s_hist);
+    if (base + kChunk <= td.numel) hist_chunk<true>(td, base, w, s_hist, count_above, above);
+    else hist_chunk<false>(td, base, w, s_hist, count_above, above);
     ++c;
   }
 }
@@ -520,21 +511,38 @@ struct BinHit {
 template <int NT>
 __device__ BinHit find_rank_from_top(const uint32_t* s_hist, uint32_t bins, uint32_t r, uint32_t* s_part,
                                      uint32_t* s_out) {
+  // level 0: every thread sums its run of bins; level 1: every lane of wavefront 0 sums a run of
+  // thread sums; a suffix scan over the 64 lanes locates the lane, then the thread, then the bin.
+  constexpr int G = NT / kWave;  // thread sums per lane of wavefront 0
   const uint32_t per = (bins + NT - 1) / NT;
   const uint32_t b0 = threadIdx.x * per;
   uint32_t sum = 0;
   for (uint32_t b = b0; b < min(b0 + per, bins); ++b) sum += s_hist[b];
   s_part[threadIdx.x] = sum;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t acc = 0;
-    int t = NT - 1;
-    for (; t > 0; --t) {
-      if (acc + s_part[t] >= r) break;
-      acc += s_part[t];
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < G; ++i) mine += s_part[lane * G + i];
+    uint32_t suffix = mine;  // sum over lanes >= this one
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const uint32_t t = __shfl_down(suffix, o);
+      if (lane + o < kWave) suffix += t;
     }
-    s_out[0] = (uint32_t)t;
-    s_out[1] = acc;
+    const unsigned long long reach = __ballot(suffix >= r);  // lanes from which the top reaches rank r
+    const int pick = reach ? 63 - __clzll(reach) : 0;         // the highest such lane holds the rank
+    if (lane == pick) {
+      uint32_t acc = suffix - mine;  // keys in lanes above
+      int t = pick * G + G - 1;
+      for (; t > pick * G; --t) {
+        if (acc + s_part[t] >= r) break;
+        acc += s_part[t];
+      }
+      s_out[0] = (uint32_t)t;
+      s_out[1] = acc;
+    }
   }
   __syncthreads();
   if (threadIdx.x == s_out[0]) {
@@ -570,137 +578,171 @@ __device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scan: one workgroup per tensor reads the tensor's histogram, clears it, and decides whether
-// theta is now exact, lies in a range whose keys are (or can be) listed, or needs a finer pass.
+// First decision after the EMA pass, one workgroup per tensor: add up the per-chunk records and
+// decide whether the listed keys settle the threshold (band hit, or small tensor) or the tensor
+// must fall back to histogram passes.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __restrict__ tds, LayerDev* layers,
-                                                          const GlobalDev* glob, uint32_t* hist, uint32_t* counters,
-                                                          StepScalars sc, uint32_t sparsity_ppm) {
+__global__ __launch_bounds__(kThreads) void k_select_begin(const TensorDesc* __restrict__ tds, LayerDev* layers,
+                                                           const GlobalDev* glob,
+                                                           const EmaPartial* __restrict__ ema_partials,
+                                                           uint32_t* counters, StepScalars sc,
+                                                           uint32_t sparsity_ppm) {
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
   if (!td.has_probe) return;
   LayerDev& ls = layers[l];
-  if (ls.mode != kSelHist) return;
-  const bool first_scan = ls.passes == 0;
-  if (td.list_all) {
-    // small tensor: every non-zero key was listed by the EMA kernel; select from the list
-    if (threadIdx.x == 0 && first_scan) {
-      const uint32_t nonzero = (uint32_t)td.numel - ls.acc_zeros;
-      ls.nonzero = nonzero;
-      ls.k_rem = topk_count(td.numel, sparsity_ppm);
+  uint32_t above = 0, zeros = 0, maxkey = 0, nonfin = 0, listed = 0;
+  for (uint32_t c = threadIdx.x; c < td.n_chunks; c += kThreads) {
+    const EmaPartial p = ema_partials[td.first_chunk + c];
+    above += p.above;
+    zeros += p.zeros;
+    maxkey = max(maxkey, p.maxkey);
+    nonfin |= p.nonfinite;
+  }
+  if (threadIdx.x < kCandLists) listed = *cand_counter(counters, l, threadIdx.x);
+  above = wave_sum(above);
+  zeros = wave_sum(zeros);
+  maxkey = wave_max(maxkey);
+  nonfin = wave_or(nonfin);
+  listed = wave_sum(listed);
+  __shared__ uint32_t s_red[5][kThreads / kWave];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  if (lane == 0) {
+    s_red[0][wave] = above;
+    s_red[1][wave] = zeros;
+    s_red[2][wave] = maxkey;
+    s_red[3][wave] = nonfin;
+    s_red[4][wave] = listed;
+  }
+  __syncthreads();
+  above = zeros = maxkey = nonfin = listed = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / kWave; ++w) {
+    above += s_red[0][w];
+    zeros += s_red[1][w];
+    maxkey = max(maxkey, s_red[2][w]);
+    nonfin |= s_red[3][w];
+    listed += s_red[4][w];
+  }
+  const uint32_t nonzero = (uint32_t)td.numel - zeros;
+  const uint32_t k = topk_count(td.numel, sparsity_ppm);
+  // 0: the lists settle it; 1: theta = 0 (fewer non-zero keys than k); 2: histogram passes
+  int outcome;
+  if (td.list_all) outcome = 0;
+  else if (k > nonzero) outcome = 1;
+  else if (ls.use_band && above < k && k <= above + listed && listed <= td.cand_cap) outcome = 0;
+  else outcome = 2;
+  if (outcome != 0) reset_cand_counters(counters, l);  // drop whatever the EMA kernel listed
+  if (threadIdx.x != 0) return;
+  ls.acc_maxkey = maxkey;
+  ls.acc_nonfinite = nonfin;
+  ls.nonzero = nonzero;
+  ls.k_rem = k;
+  ls.passes = 1;
+  ls.acc_above = 0;
+  if (outcome == 0) {
+    ls.mode = kSelCand;
+    ls.mask_done = 1;
+    if (td.list_all) {
       ls.above = 0;
-      ls.mode = kSelCand;
       ls.rng_lo = 0;
       ls.rng_hi = 0x80000000u;
-      ls.mask_done = 1;
-      ls.passes = 1;
+    } else {
+      ls.above = above;
+      ls.rng_lo = ls.band_lo;
+      ls.rng_hi = ls.band_hi;
+      ls.dens_count = listed;
+      ls.dens_width = ls.band_hi - ls.band_lo;
     }
-    return;
+  } else if (outcome == 1) {
+    ls.mode = kSelExact;
+    ls.mask_done = 0;
+    ls.theta_key = 0;
+    ls.above = nonzero;
+    ls.sel_count = 0;
+  } else {
+    // histogram over the predicted window if there is one, else over the full key range
+    ls.mode = kSelHist;
+    ls.mask_done = 0;
+    ls.above = 0;
+    ls.count_above = ls.predicted;
+    if (!ls.predicted) {
+      ls.win_lo = 0;
+      ls.win_shift = kFullShift;
+      ls.win_bins = kHistBins;
+    }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scan after a histogram pass: one workgroup per tensor reads the tensor's histogram, clears it,
+// and decides whether theta is now exact, lies in a range whose keys can be listed by the mask
+// pass, or needs a finer histogram.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __restrict__ tds, LayerDev* layers,
+                                                          const GlobalDev* glob, uint32_t* hist, StepScalars sc) {
+  if (step_skipped(glob, sc.step_id)) return;
+  const uint32_t l = blockIdx.x;
+  const TensorDesc td = tds[l];
+  if (!td.has_probe) return;
+  LayerDev& ls = layers[l];
+  if (ls.mode != kSelHist || ls.passes == 0) return;
   __shared__ uint32_t s_hist[kHistBins];
   __shared__ uint32_t s_part[kThreads];
   __shared__ uint32_t s_out[8];
   const uint32_t bins = ls.win_bins, lo = ls.win_lo, shift = ls.win_shift;
-  const uint32_t band_lo = ls.band_lo, band_hi = ls.band_hi;
-  const bool use_band = first_scan && ls.use_band != 0;
   uint32_t* gh = hist + (size_t)l * kHistBins;
-  uint32_t local = 0, in_band = 0;
+  uint32_t local = 0;
   for (uint32_t b = threadIdx.x; b < kHistBins; b += kThreads) {
     const uint32_t v = (b < bins) ? gh[b] : 0u;
     s_hist[b] = v;
     local += v;
-    const uint32_t key0 = lo + (b << shift);
-    if (use_band && b < bins && key0 >= band_lo && key0 < band_hi) in_band += v;
     if (v) gh[b] = 0;
   }
   local = wave_sum(local);
-  in_band = wave_sum(in_band);
-  if ((threadIdx.x & (kWave - 1)) == 0) {
-    s_part[threadIdx.x / kWave] = local;
-    s_part[4 + threadIdx.x / kWave] = in_band;
-  }
+  if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = local;
   __syncthreads();
   const uint32_t in_window = s_part[0] + s_part[1] + s_part[2] + s_part[3];
-  const uint32_t band_total = s_part[4] + s_part[5] + s_part[6] + s_part[7];
   __syncthreads();
-
-  uint32_t k, above;
-  if (first_scan) {
-    const uint32_t nonzero = (uint32_t)td.numel - ls.acc_zeros;
-    k = topk_count(td.numel, sparsity_ppm);
-    above = ls.acc_above;
-    if (k > nonzero) {  // fewer non-zero magnitudes than k: theta = 0, every non-zero entry is kept
-      if (threadIdx.x == 0) {
-        ls.nonzero = nonzero;
-        ls.mode = kSelExact;
-        ls.theta_key = 0;
-        ls.above = nonzero;
-        ls.sel_count = 0;
-        ls.k_rem = k;
-        ls.passes = 1;
-        ls.mask_done = 0;
-      }
-      reset_cand_counters(counters, l);
-      return;
-    }
-    if (threadIdx.x == 0) ls.nonzero = nonzero;
-  } else {
-    k = ls.k_rem;
-    above = ls.above;
-  }
-  // miss of a predicted window: theta lies above or below it -> restart with the full key range
+  const uint32_t k = ls.k_rem;
+  const uint32_t above = ls.count_above ? ls.acc_above : ls.above;  // counted by this pass, or known
+  // the window (a predicted one) does not contain theta: restart with the full key range
   if (above >= k || above + in_window < k) {
     if (threadIdx.x == 0) {
-      ls.mode = kSelHist;
       ls.win_lo = 0;
       ls.win_shift = kFullShift;
       ls.win_bins = kHistBins;
       ls.above = 0;
-      ls.k_rem = k;
-      ls.passes = 1;
-      ls.mask_done = 0;
+      ls.acc_above = 0;
+      ls.count_above = 0;
+      ls.passes = ls.passes + 1;
       ls.window_missed = 1;
     }
-    if (first_scan) reset_cand_counters(counters, l);
     return;
   }
   const BinHit hit = find_rank_from_top<kThreads>(s_hist, bins, k - above, s_part, s_out);
+  if (threadIdx.x != 0) return;
   const uint32_t new_lo = lo + (hit.bin << shift);
-  const uint32_t new_hi = new_lo + (1u << shift);
-  const bool band_ok = use_band && new_lo >= band_lo && new_hi <= band_hi && band_total <= td.cand_cap;
-  if (first_scan && !band_ok) reset_cand_counters(counters, l);  // drop whatever the EMA kernel listed
-  if (threadIdx.x == 0) {
-    const uint32_t new_above = above + hit.higher;
-    ls.above = new_above;
-    ls.k_rem = k;
-    ls.sel_count = hit.count;
-    ls.dens_count = hit.count;
-    ls.dens_shift = shift;
-    ls.passes = ls.passes + 1;
-    if (band_ok) {
-      // the provisional mask is right outside the band and every key of the band is listed
-      ls.mode = kSelCand;
-      ls.rng_lo = new_lo;
-      ls.rng_hi = new_hi;
-      ls.mask_done = 1;
-    } else {
-      if (first_scan) ls.mask_done = 0;
-      if (shift == 0) {
-        ls.mode = kSelExact;
-        ls.theta_key = new_lo;
-      } else if (hit.count <= td.cand_cap) {
-        ls.mode = kSelCand;
-        ls.rng_lo = new_lo;
-        ls.rng_hi = new_hi;
-      } else {
-        const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
-        ls.mode = kSelHist;
-        ls.win_lo = new_lo;
-        ls.win_shift = ns;
-        ls.win_bins = 1u << (shift - ns);
-      }
-    }
+  ls.above = above + hit.higher;
+  ls.acc_above = 0;
+  ls.count_above = 0;
+  ls.sel_count = hit.count;
+  ls.dens_count = hit.count;
+  ls.dens_width = 1u << shift;
+  ls.passes = ls.passes + 1;
+  if (shift == 0) {
+    ls.mode = kSelExact;
+    ls.theta_key = new_lo;
+  } else if (hit.count <= td.cand_cap) {
+    ls.mode = kSelCand;
+    ls.rng_lo = new_lo;
+    ls.rng_hi = new_lo + (1u << shift);
+  } else {
+    const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
+    ls.win_lo = new_lo;
+    ls.win_shift = ns;
+    ls.win_bins = 1u << (shift - ns);
   }
 }
 
@@ -745,10 +787,10 @@ __device__ __forceinline__ void mask_chunk(const TensorDesc& td, int64_t base, u
 }
 
 // ---------------------------------------------------------------------------------------------
-// Finish: one workgroup per tensor resolves theta among the listed candidates (radix select in
-// LDS), sets their mask bits, publishes theta / nnz / lambda and plans the next probed step:
-// the window is centred on the threshold extrapolated from the last two, its bin width and the
-// band width follow the error the last predictions made.
+// Finish: one workgroup per tensor resolves theta among the listed keys (radix select in LDS),
+// sets their mask bits, publishes theta / nnz and plans the next probed step: the band and the
+// fallback window are centred on the threshold extrapolated from the last two; their widths
+// follow the error the last predictions made.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t abs_diff(uint32_t a, uint32_t b) { return a > b ? a - b : b - a; }
 
@@ -790,14 +832,14 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   uint32_t nnz = above + ls.sel_count;
   if (mode == kSelExact && theta == 0u) nnz = ls.nonzero;
   if (mode == kSelCand) {
+    // all listed keys lie in [rng_lo, rng_hi); select inside the enclosing power-of-two range
     uint32_t lo = rng_lo;
-    uint32_t width_shift = 31u - (uint32_t)__clz(rng_hi - rng_lo);  // range width is a power of two
+    const uint32_t width = rng_hi - rng_lo;
+    uint32_t width_shift = 32u - (uint32_t)__clz(width - 1u);  // ceil(log2(width)), width >= 2
+    if (width <= 1u) width_shift = 0;
     uint32_t r = ls.k_rem - above;
-    // number of listed keys inside the range (the lists may also hold band keys outside it)
     uint32_t inside = 0;
-    for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
-      inside += (c.key >= rng_lo && c.key < rng_hi) ? 1u : 0u;
-    });
+    for (uint32_t i = threadIdx.x; i <= kCandLists; i += kFinishThreads) inside += s_counts[i];
     inside = finish_block_sum(inside, s_red);
     if (r > inside) {
       theta = 0;  // fewer non-zero keys than k (small tensors only): keep every non-zero entry
@@ -808,7 +850,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
         for (uint32_t b = threadIdx.x; b < bins; b += kFinishThreads) s_hist[b] = 0;
         __syncthreads();
         for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
-          if (c.key >= lo && ((c.key - lo) >> width_shift) == 0u) atomicAdd(&s_hist[(c.key - lo) >> ns], 1u);
+          if (c.key >= lo && ((uint64_t)(c.key - lo) >> width_shift) == 0u) atomicAdd(&s_hist[(c.key - lo) >> ns], 1u);
         });
         __syncthreads();
         const BinHit hit = find_rank_from_top<kFinishThreads>(s_hist, bins, r, s_part, s_out);
@@ -818,19 +860,16 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
       }
       theta = lo;
     }
-  }
-  // Listed keys had their bits left clear: set those at or above theta.  Keys above the range
-  // are already counted in `above`.
-  if (mode == kSelCand || ls.mask_done) {
+    // listed keys had their bits left clear: set those at or above theta
     uint32_t kept = 0;
     for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
       if (c.key >= theta) {
         atomicOr(&td.mask[c.idx >> 5], 1u << (c.idx & 31u));
-        kept += (c.key >= rng_lo && c.key < rng_hi) ? 1u : 0u;
+        ++kept;
       }
     });
     kept = finish_block_sum(kept, s_red);
-    if (mode == kSelCand) nnz = above + kept;
+    nnz = above + kept;
   }
   __syncthreads();
   reset_cand_counters(counters, l);
@@ -857,23 +896,21 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   // centre: linear extrapolation in key space from the last two thresholds
   int64_t centre = (int64_t)theta;
   if (have >= 1) centre += (int64_t)theta - (int64_t)prev;
-  if (centre < 0) centre = 0;
+  if (centre < 1) centre = 1;
   if (centre > 0x7f7fffff) centre = 0x7f7fffff;
-  // bins: the half window (1024 bins) spans 32 e
+  // fallback window: 2048 bins whose half (1024 bins) spans 32 e
   uint32_t s = kMinPredShift;
   while (s < kFullShift && ((uint64_t)1024 << s) < (uint64_t)32 * e) ++s;
   const uint32_t cbin = (uint32_t)centre >> s;
   const uint32_t lo_bin = cbin > (uint32_t)(kHistBins / 2) ? cbin - kHistBins / 2 : 0u;
-  // band: 4 e on either side, whole bins, inside the window
-  uint32_t hb = (uint32_t)(((uint64_t)4 * e + ((uint64_t)1 << s) - 1) >> s);
-  if (hb < 1) hb = 1;
-  if (hb > 512) hb = 512;
-  const uint32_t band_lo_bin = cbin > hb ? cbin - hb : 0u;
-  const uint32_t band_lo = max(band_lo_bin, lo_bin) << s;
-  const uint32_t band_hi = (cbin + hb + 1) << s;
+  // band: 4 e on either side of the centre
+  const uint64_t half = (uint64_t)4 * e;
+  const uint32_t band_lo = (uint64_t)centre > half ? (uint32_t)((uint64_t)centre - half) : 1u;
+  const uint64_t hi64 = (uint64_t)centre + half + 1;
+  const uint32_t band_hi = hi64 < 0x7f800000ull ? (uint32_t)hi64 : 0x7f800000u;
   // expected number of keys inside the band, from the key density around this step's threshold;
   // listing them only pays when they fit the lists with room to spare
-  const uint64_t expect = ((uint64_t)(band_hi - band_lo) * ls.dens_count) >> ls.dens_shift;
+  const uint64_t expect = ls.dens_width ? ((uint64_t)(band_hi - band_lo) * ls.dens_count) / ls.dens_width : 0u;
   ls.mode = kSelHist;
   ls.win_lo = lo_bin << s;
   ls.win_shift = s;
@@ -890,11 +927,9 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   ls.k_rem = 0;
   ls.sel_count = 0;
   ls.dens_count = 0;
-  ls.dens_shift = 0;
+  ls.dens_width = 0;
   ls.acc_above = 0;
   ls.acc_zeros = 0;
-  ls.acc_maxkey = 0;
-  ls.acc_nonfinite = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1166,26 +1201,30 @@ hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipSt
   return hipSuccess;
 }
 
-hipError_t launch_curv_ema_hist(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h,
-                                hipStream_t s) {
-  const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
-  hipLaunchKernelGGL(k_curv_ema_hist, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks,
-                     t.layers, t.glob, t.hist, t.cands, t.cand_counters, sc, beta_h, omb_h);
+hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s) {
+  hipLaunchKernelGGL(k_curv_ema, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
+                     t.ema_partials, t.cands, t.cand_counters, sc, beta_h, omb_h);
+  TA_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t launch_select_begin(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s) {
+  hipLaunchKernelGGL(k_select_begin, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                     t.ema_partials, t.cand_counters, sc, sparsity_ppm);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
-  const uint32_t grid = t.total_chunks < t.fallback_grid ? t.total_chunks : t.fallback_grid;
+  const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_hist_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
                      t.glob, t.hist, sc);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s) {
-  hipLaunchKernelGGL(k_select_scan, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.hist,
-                     t.cand_counters, sc, sparsity_ppm);
+hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+  hipLaunchKernelGGL(k_select_scan, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.hist, sc);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

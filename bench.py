@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tensors", type=int, default=0, help="use only the first N tensors of the workload (tuning runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the library's plain fp32 copy kernel on 1 GiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -93,6 +95,16 @@ def main():
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {L} tensors, {N} params, {R} input sets resident, "
           f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated", file=sys.stderr, flush=True)
+
+    if args.calibrate_copy:
+        # 2^28 floats: reads 1 GiB, writes 1 GiB, five launches
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            ta.triaccel_cast_f32(src.data_ptr(), dst.data_ptr(), src.numel(), ta.FP32,
+                                 torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
 
     opt.set_profiling(True)
     lr = float(hyper["lr"])

@@ -145,7 +145,9 @@ class OracleTriAccel:
 
     def step(self, grads: Sequence[np.ndarray], zs: Sequence[Optional[np.ndarray]],
              hzs: Sequence[Optional[np.ndarray]], lr: float, loss_scale: float, batch_size: int,
-             mem_used: int, mem_total: int) -> dict:
+             mem_used: int, mem_total: int, overflow_elsewhere: bool = False) -> dict:
+        """``overflow_elsewhere``: a tensor that this oracle does not hold (when it tracks a subset
+        of a larger parameter set) had a non-finite gradient, so the step is skipped for all."""
         L, cfg = lib(), self.cfg
         f32 = np.float32
         inv_scale = f32(1.0) / f32(loss_scale)
@@ -154,7 +156,7 @@ class OracleTriAccel:
         # overflow detection on the stored gradients; all-or-nothing skip
         for t, g in zip(self.tensors, grads):
             t.found_inf = int(L.oracle_found_nonfinite(g.ctypes.data, t.grad_dtype, t.numel))
-        skipped = int(any(t.found_inf for t in self.tensors))
+        skipped = int(any(t.found_inf for t in self.tensors) or overflow_elsewhere)
 
         if not skipped:
             self.applied_steps += 1

@@ -1,0 +1,109 @@
+"""Parity at the full sizes of the two large workloads, in the launch configuration bench.py
+times: the oracle follows a sample of whole tensors element by element (tensors are independent
+once the skip decision is known), and every tensor is checked through properties that hold at
+any size and are evaluated with plain PyTorch operations on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_16905_amd as ta
+from workloads import get_workload
+from workloads.configs import FP32, TORCH_DTYPE
+from _gpu_harness import bits_equal, same_or_both_nan
+from _runner import to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def popcount_words(mask: torch.Tensor) -> int:
+    b = mask.view(torch.uint8)
+    table = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=mask.device)
+    return int(table[b.long()].sum().item())
+
+
+def check_properties(opt, l, st, k):
+    """Invariants of the threshold / mask that need no oracle."""
+    a = opt.curv[l].abs()
+    theta = torch.tensor(st.theta, dtype=torch.float32, device=a.device)
+    ge = int(((a >= theta) & (a > 0)).sum().item())
+    gt = int((a > theta).sum().item())
+    assert st.nnz == ge == popcount_words(opt.mask[l]), (l, st.nnz, ge)
+    if st.theta > 0.0:
+        assert gt < k <= ge, (l, gt, k, ge)  # theta is the k-th largest magnitude
+    else:
+        assert ge < k, (l, ge, k)            # fewer non-zero magnitudes than k: all of them are kept
+    assert st.lambda_ == float(a.max().item())
+
+
+def run_sampled(wl, sample, steps, dev, check_all_every=1):
+    L = wl.n_tensors
+    params = [wl.init_param(l, device=dev) for l in range(L)]
+    opt = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype)
+    cfg = oracle.OracleConfig.from_hyper(wl.hyper)
+    orc = oracle.OracleTriAccel(cfg, [to_numpy(params[l]) for l in sample], [wl.init_dtype(l) for l in sample],
+                                [wl.grad_dtype] * len(sample), workers=len(sample))
+    del params
+    scale, batch = float(wl.hyper["loss_scale"]), int(wl.hyper["batch_size"])
+    skipped_steps = []
+    for t in range(1, steps + 1):
+        grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
+        pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
+        zs, hzs = [p[0] for p in pr], [p[1] for p in pr]
+        del pr
+        opt.step(grads, zs, hzs, lr=wl.hyper["lr"], loss_scale=scale, batch_size=batch, mem_used_bytes=8,
+                 mem_total_bytes=10)
+        res = opt.result()
+        # overflow in tensors the oracle does not hold, found with a library reduction
+        elsewhere = any((not bool(torch.isfinite(grads[l]).all())) for l in range(L) if l not in sample)
+        ro = orc.step([to_numpy(grads[l]) for l in sample], [to_numpy(zs[l]) for l in sample],
+                      [to_numpy(hzs[l]) for l in sample], wl.hyper["lr"], scale, batch, 8, 10,
+                      overflow_elsewhere=elsewhere)
+        assert res.skipped == ro["skipped"], (t, res.skipped, ro["skipped"])
+        assert res.next_loss_scale == ro["next_loss_scale"] and res.next_batch_size == ro["next_batch_size"]
+        skipped_steps.append(res.skipped)
+        st = opt.layer_state()
+        for o, l in zip(orc.tensors, sample):
+            g = st[l]
+            w = f"{wl.name} step {t} tensor {l}"
+            assert (g.code, g.prev_code, g.found_inf, g.nnz) == (o.code, o.prev_code, o.found_inf, o.nnz), w
+            for gv, ov in ((g.theta, o.theta), (g.lambda_, o.lam), (g.eta, o.eta)):
+                assert np.float32(gv).view(np.uint32) == np.float32(ov).view(np.uint32), w
+            sd = float(np.sqrt(max(float(o.var), 0.0)))
+            assert abs(g.mean - float(o.mean)) <= 1e-5 * max(abs(float(o.mean)), sd) + 1e-45, w
+            assert abs(g.var - float(o.var)) <= 1e-5 * abs(float(o.var)) + 1e-45, w
+            assert abs(g.v - float(o.v)) <= 1e-5 * abs(float(o.v)) + 1e-45, w
+            assert bits_equal(opt.mask[l].cpu().numpy().view(np.uint32), o.mask), w + " mask"
+            assert bits_equal(opt.curv[l].cpu().numpy(), o.curv), w + " curvature"
+            assert same_or_both_nan(opt.mom[l].cpu().numpy(), o.mom), w + " momentum"
+            gp, op = to_numpy(opt.param(l, g.code)), o.param_view()
+            assert (same_or_both_nan(gp, op) if o.code == FP32 else bits_equal(gp, op)), w + " parameters"
+        if not res.skipped and t % check_all_every == 0:
+            for l in range(L):
+                n = wl.numel(l)
+                k = max(1, min(n, n - (n * int(wl.hyper["sparsity_ppm"])) // 1000000))
+                check_properties(opt, l, st[l], k)
+        print(f"{wl.name}: step {t} ok (skipped={res.skipped}, loss scale {scale})", flush=True)
+        scale, batch = ro["next_loss_scale"], ro["next_batch_size"]
+        del grads, zs, hzs
+    codes = [s.code for s in opt.layer_state()]
+    opt.close()
+    return skipped_steps, codes
+
+
+def test_large_streaming_full_size_sampled_tensors():
+    wl = get_workload("large_streaming")
+    assert wl.total_params == 1073741824
+    skipped, codes = run_sampled(wl, sample=[0, 37, 63], steps=3, dev=torch.device("cuda:0"))
+    assert skipped == [0, 0, 0] and len(set(codes)) >= 2
+
+
+def test_mixed_state_full_size_sampled_tensors_with_overflow():
+    wl = get_workload("mixed_state")
+    assert wl.total_params == 352321536
+    inj7, inj14 = wl.injected_tensor(7), wl.injected_tensor(14)
+    sample = sorted({0, 1, 2, 5, 47, 95, inj7})  # both shapes, all three initial dtypes, one injected tensor
+    skipped, codes = run_sampled(wl, sample=sample, steps=15, dev=torch.device("cuda:0"), check_all_every=5)
+    assert skipped[6] == 1 and skipped[13] == 1
+    assert inj14 not in sample  # the second injection hits a tensor the oracle does not hold
+    assert set(codes) == {0, 1, 2}

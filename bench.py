@@ -88,9 +88,12 @@ def main():
     del params
     R = max(1, min(args.input_sets, K + W))
     sets = []
-    for r in range(R):
-        grads = [wl.grad(r + 1, l, scale, device=dev) for l in range(L)]
-        pr = [wl.probe(r + 1, l, scale, device=dev) for l in range(L)]
+    # generator steps to draw the input batches from (steps with injected inf/NaN are left out:
+    # a skipped step does no work and would flatter the average)
+    gen_steps = [t for t in range(1, 4 * R + 2) if not (wl.inject_every and t % wl.inject_every == 0)][:R]
+    for t in gen_steps:
+        grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
+        pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
         sets.append((grads, [p[0] for p in pr], [p[1] for p in pr]))
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {L} tensors, {N} params, {R} input sets resident, "

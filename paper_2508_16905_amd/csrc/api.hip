@@ -200,7 +200,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
     d.cand_offset = cand_total;
     d.cand_cap = t.numel < (int64_t)kCandCap ? (uint32_t)t.numel : kCandCap;
     d.sub_cap = (d.cand_cap + kCandLists - 1) / kCandLists;
-    d.list_all = t.numel <= (int64_t)kCandCap ? 1u : 0u;
+    d.list_all = t.numel <= (int64_t)kListAllMax ? 1u : 0u;
     cand_total += (uint64_t)kCandLists * d.sub_cap + d.cand_cap;
     for (uint32_t k = 0; k < nc; ++k) chunks.push_back(ChunkRef{(uint32_t)i, k});
     if (nc > max_chunks) max_chunks = nc;

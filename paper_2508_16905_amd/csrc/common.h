@@ -22,6 +22,8 @@ constexpr uint32_t kFullShift = 20;          // 2048 bins of 2^20 keys cover all
 constexpr uint32_t kMinPredShift = 6;        // finest predicted window: 2048 bins of 64 keys
 constexpr uint32_t kUnknownPredErr = 1u << 16;  // assumed prediction error (keys) before any is measured
 constexpr uint32_t kCandCap = 65536;         // keys a tensor may list in total (entries)
+constexpr uint32_t kListAllMax = 8192;       // tensors up to this size list every non-zero key (no prediction)
+constexpr int kFinishRegs = 8;               // listed keys per thread the finish kernel can hold in registers
 constexpr uint32_t kCandLists = 64;          // sub-lists per tensor (plus one overflow list)
 constexpr uint32_t kCandCounterStride = 32;  // words between list counters: one 128-byte line each
 
@@ -65,7 +67,7 @@ struct TensorDesc {
   uint64_t cand_offset;  // first entry of the tensor's candidate lists in the pool
   uint32_t cand_cap;     // min(numel, kCandCap): capacity of the overflow list
   uint32_t sub_cap;      // capacity of each of the kCandLists sub-lists: ceil(cand_cap / kCandLists)
-  uint32_t list_all;     // numel <= kCandCap: every non-zero key is listed, no histogram
+  uint32_t list_all;     // numel <= kListAllMax: every non-zero key is listed, no prediction
   uint32_t pad_;
 };
 

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
 //     the listed keys resolve theta exactly and only their mask bits are patched.
 //   * Otherwise (no prediction yet, prediction off, too many keys to list) the tensor falls
 //     back to a radix select by histogram passes over h and a separate mask pass.
-//   * Tensors with at most kCandCap elements list all their non-zero keys and select from the list.
+//   * Tensors with at most kListAllMax elements list all their non-zero keys and select from the list.
 // ---------------------------------------------------------------------------------------------
 struct Window {
   uint32_t lo, shift, bins;
@@ -820,6 +820,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   __shared__ uint32_t s_red[kFinishThreads / kWave];
   __shared__ uint32_t s_out[8];
   __shared__ uint32_t s_counts[kCandLists + 1];
+  __shared__ uint32_t s_prefix[kCandLists + 2];
   if (threadIdx.x <= kCandLists) {
     const uint32_t c = *cand_counter(counters, l, threadIdx.x);
     s_counts[threadIdx.x] = min(c, threadIdx.x < kCandLists ? td.sub_cap : td.cand_cap);
@@ -838,9 +839,48 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
     uint32_t width_shift = 32u - (uint32_t)__clz(width - 1u);  // ceil(log2(width)), width >= 2
     if (width <= 1u) width_shift = 0;
     uint32_t r = ls.k_rem - above;
-    uint32_t inside = 0;
-    for (uint32_t i = threadIdx.x; i <= kCandLists; i += kFinishThreads) inside += s_counts[i];
-    inside = finish_block_sum(inside, s_red);
+    // exclusive prefix sums of the list lengths (flat numbering of the listed keys)
+    if (threadIdx.x == 0) {
+      uint32_t acc = 0;
+      for (uint32_t i = 0; i <= kCandLists; ++i) {
+        s_prefix[i] = acc;
+        acc += s_counts[i];
+      }
+      s_prefix[kCandLists + 1] = acc;
+    }
+    __syncthreads();
+    const uint32_t inside = s_prefix[kCandLists + 1];
+    // up to kFinishRegs keys per thread are held in registers for the passes below; longer lists
+    // are re-read from memory in every pass
+    const bool in_regs = inside <= (uint32_t)(kFinishThreads * kFinishRegs);
+    Candidate reg[kFinishRegs];
+    uint32_t have = 0;
+    if (in_regs) {
+#pragma unroll
+      for (int i = 0; i < kFinishRegs; ++i) {
+        const uint32_t f = (uint32_t)i * kFinishThreads + threadIdx.x;
+        reg[i] = Candidate{0u, 0u};
+        if (f < inside) {
+          uint32_t a = 0, b = kCandLists + 1;  // s_prefix[a] <= f < s_prefix[b]
+          while (b - a > 1) {
+            const uint32_t m = (a + b) >> 1;
+            if (s_prefix[m] <= f) a = m;
+            else b = m;
+          }
+          reg[i] = cands[td.cand_offset + (size_t)a * td.sub_cap + (f - s_prefix[a])];
+          have |= 1u << i;
+        }
+      }
+    }
+    auto visit = [&](auto f) {
+      if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < kFinishRegs; ++i)
+          if (have & (1u << i)) f(reg[i]);
+      } else {
+        for_each_candidate<kFinishThreads>(td, cands, s_counts, f);
+      }
+    };
     if (r > inside) {
       theta = 0;  // fewer non-zero keys than k (small tensors only): keep every non-zero entry
     } else {
@@ -849,7 +889,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
         const uint32_t bins = 1u << (width_shift - ns);
         for (uint32_t b = threadIdx.x; b < bins; b += kFinishThreads) s_hist[b] = 0;
         __syncthreads();
-        for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
+        visit([&](const Candidate& c) {
           if (c.key >= lo && ((uint64_t)(c.key - lo) >> width_shift) == 0u) atomicAdd(&s_hist[(c.key - lo) >> ns], 1u);
         });
         __syncthreads();
@@ -862,7 +902,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
     }
     // listed keys had their bits left clear: set those at or above theta
     uint32_t kept = 0;
-    for_each_candidate<kFinishThreads>(td, cands, s_counts, [&](const Candidate& c) {
+    visit([&](const Candidate& c) {
       if (c.key >= theta) {
         atomicOr(&td.mask[c.idx >> 5], 1u << (c.idx & 31u));
         ++kept;

@@ -1,0 +1,148 @@
+"""GPU tests of the C ABI's contract: argument errors change no state, pointers may change from
+call to call, results are deterministic, several handles coexist, profiling returns stage times."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_16905_amd as ta
+from paper_2508_16905_amd import binding as B
+from workloads import get_workload
+from workloads.configs import FP32
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def make(wl, seed_shift=0):
+    params = [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)]
+    return ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype)
+
+
+def inputs(wl, t):
+    g = [wl.grad(t, l).to(DEV) for l in range(wl.n_tensors)]
+    pr = [wl.probe(t, l) for l in range(wl.n_tensors)]
+    return g, [p[0].to(DEV) for p in pr], [p[1].to(DEV) for p in pr]
+
+
+def snapshot(opt):
+    torch.cuda.synchronize()
+    return [(opt.buf[i].clone(), opt.curv[i].clone(), opt.mom[i].clone(), opt.mask[i].clone()) for i in range(opt.n)]
+
+
+def equal(a, b):
+    return all(torch.equal(x, y) for ta_, tb in zip(a, b) for x, y in zip(ta_, tb))
+
+
+def test_argument_errors_are_reported_and_change_nothing():
+    wl = get_workload("tiny_mlp")
+    opt = make(wl)
+    g, z, hz = inputs(wl, 1)
+    opt.step(g, z, hz)
+    opt.result()
+    before = snapshot(opt)
+    lib = ta.load_library()
+    args = B.StepArgs(C.sizeof(B.StepArgs), 0.1, 1.0, 96, 8, 10)
+
+    def call(mutate, n=None):
+        arr = (B.Tensor * opt.n)()
+        for i in range(opt.n):
+            C.memmove(C.byref(arr[i]), C.byref(opt._tensors[i]), C.sizeof(B.Tensor))
+        mutate(arr)
+        return lib.triaccel_step(opt.handle, arr, opt.n if n is None else n, C.byref(args))
+
+    assert call(lambda a: setattr(a[1], "grad", a[1].grad + 4)) == -5          # misaligned
+    assert call(lambda a: setattr(a[0], "param", None)) == -4                  # NULL pointer
+    assert call(lambda a: setattr(a[2], "hz", None)) == -4                     # z without hz
+    assert call(lambda a: setattr(a[2], "numel", a[2].numel + 1)) == -3        # shape changed
+    assert call(lambda a: setattr(a[3], "grad_dtype", 1)) == -3                # dtype changed
+    assert call(lambda a: None, n=opt.n - 1) == -3                             # wrong count
+    bad = B.StepArgs(C.sizeof(B.StepArgs), 0.1, 0.0, 96, 8, 10)                # loss scale must be > 0
+    assert lib.triaccel_step(opt.handle, opt._tensors, opt.n, C.byref(bad)) == -1
+    bad = B.StepArgs(4, 0.1, 1.0, 96, 8, 10)                                   # wrong struct_size
+    assert lib.triaccel_step(opt.handle, opt._tensors, opt.n, C.byref(bad)) == -1
+    res = opt.result()
+    assert res.step_index == 1 and equal(before, snapshot(opt))
+    # init-time errors
+    cfg = B.Config.from_hyper(wl.hyper)
+    cfg.beta_var = 1.0
+    handle = C.c_void_p()
+    assert lib.triaccel_init(C.byref(handle), C.byref(cfg), opt._tensors, opt.n, None) == -1 and not handle
+    cfg = B.Config.from_hyper(wl.hyper)
+    arr = (B.Tensor * opt.n)()
+    for i in range(opt.n):
+        C.memmove(C.byref(arr[i]), C.byref(opt._tensors[i]), C.sizeof(B.Tensor))
+    arr[0].param_dtype = 7
+    assert lib.triaccel_init(C.byref(handle), C.byref(cfg), arr, opt.n, None) == -2
+    opt.close()
+
+
+def test_result_before_any_step_and_profiling_calls():
+    wl = get_workload("tiny_mlp")
+    opt = make(wl)
+    lib = ta.load_library()
+    res = B.StepResult()
+    res.struct_size = C.sizeof(B.StepResult)
+    assert lib.triaccel_result(opt.handle, C.byref(res)) == -7
+    g, z, hz = inputs(wl, 1)
+    opt.step(g, z, hz)
+    with pytest.raises(ta.TriAccelError):
+        opt.stage_times()  # profiling was off
+    opt.set_profiling(True)
+    opt.step(g, z, hz)
+    times = opt.stage_times()
+    assert len(times) == len(ta.STAGE_NAMES) and all(t >= 0 for t in times) and sum(times) > 0
+    opt.close()
+
+
+def test_two_runs_are_bit_identical_and_pointers_may_change():
+    # determinism (no floating-point atomics, fixed merge orders) and fresh input buffers every step
+    wl = get_workload("resnet18")
+    a, b = make(wl), make(wl)
+    for t in range(1, 5):
+        ga, za, hza = inputs(wl, t)
+        gb, zb, hzb = [x.clone() for x in ga], [x.clone() for x in za], [x.clone() for x in hza]
+        a.step(ga, za, hza)
+        b.step(gb, zb, hzb)
+        ra, rb = a.result(), b.result()
+        assert (ra.skipped, ra.next_loss_scale) == (rb.skipped, rb.next_loss_scale)
+        sa, sb = a.layer_state(), b.layer_state()
+        for x, y in zip(sa, sb):
+            assert bytes(x) == bytes(y)
+    assert equal(snapshot(a), snapshot(b))
+    a.close()
+    b.close()
+
+
+def test_step_on_a_side_stream():
+    wl = get_workload("tiny_mlp")
+    stream = torch.cuda.Stream(device=DEV)
+    params = [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)]
+    ref = make(wl)
+    with torch.cuda.stream(stream):
+        opt = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype, stream=stream)
+    for t in range(1, 4):
+        g, z, hz = inputs(wl, t)
+        torch.cuda.synchronize()
+        opt.step(g, z, hz)
+        ref.step(g, z, hz)
+        opt.result()
+        ref.result()
+    assert equal(snapshot(opt), snapshot(ref))
+    opt.close()
+    ref.close()
+
+
+def test_memory_numbers_from_the_runtime_when_not_supplied():
+    wl = get_workload("tiny_mlp")
+    opt = make(wl)
+    g, z, hz = inputs(wl, 1)
+    opt.step(g, z, hz, batch_size=96, mem_used_bytes=0, mem_total_bytes=0)
+    res = opt.result()
+    free, total = torch.cuda.mem_get_info()
+    used = total - free
+    want = 112 if used < 0.7 * total else (80 if used > 0.9 * total else 96)
+    assert res.next_batch_size == want
+    opt.close()

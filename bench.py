@@ -45,7 +45,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="large_streaming")
     ap.add_argument("--all-fp32", action="store_true", help="thresholds that keep every layer in FP32")
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")

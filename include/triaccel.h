@@ -125,6 +125,10 @@ typedef struct {
   uint32_t curv_nonfinite; /* a probe sample was non-finite at the last probed step (element frozen) */
   uint32_t sel_passes;  /* diagnostic: passes over h, beyond the one that updates it, that the threshold
                            selection of the last probed step needed (0 when the prediction held)        */
+  uint32_t sel_listed;  /* diagnostic: keys listed by the curvature kernel at the last probed step          */
+  uint32_t sel_outcome; /* diagnostic: 0 small tensor (all keys listed), 1 predicted band held, 2 no band
+                           this step, 3 threshold above the band, 4 below it, 5 too many keys listed,
+                           6 fewer non-zero magnitudes than k                                              */
 } triaccel_layer_info;
 
 /* Stage timings of one step (only recorded while profiling is on). */

@@ -105,6 +105,8 @@ class LayerInfo(C.Structure):
         ("found_inf", C.c_uint32),
         ("curv_nonfinite", C.c_uint32),
         ("sel_passes", C.c_uint32),
+        ("sel_listed", C.c_uint32),
+        ("sel_outcome", C.c_uint32),
     ]
 
 

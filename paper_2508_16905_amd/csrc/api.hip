@@ -213,6 +213,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
     ls.win_lo = 0;
     ls.win_shift = kFullShift;
     ls.win_bins = kHistBins;
+    ls.var_ext = 3.0e38f;  // no extrapolation error measured yet
   }
   DeviceTables& T = c->t;
   T.n_tensors = (uint32_t)n;
@@ -387,6 +388,8 @@ int triaccel_layer_state(triaccel_handle h, triaccel_layer_info* out, int32_t n)
     o.found_inf = ls.found_inf;
     o.curv_nonfinite = ls.curv_nonfinite;
     o.sel_passes = ls.sel_passes;
+    o.sel_listed = ls.sel_listed;
+    o.sel_outcome = ls.sel_outcome;
   }
   return TRIACCEL_OK;
 }

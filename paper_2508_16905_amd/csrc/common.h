@@ -21,7 +21,7 @@ constexpr int kHistBits = 11;
 constexpr uint32_t kFullShift = 20;          // 2048 bins of 2^20 keys cover all 2^31 keys
 constexpr uint32_t kMinPredShift = 6;        // finest predicted window: 2048 bins of 64 keys
 constexpr uint32_t kUnknownPredErr = 1u << 16;  // assumed prediction error (keys) before any is measured
-constexpr uint32_t kCandCap = 65536;         // keys a tensor may list in total (entries)
+constexpr uint32_t kCandCap = 262144;        // keys a tensor may list in total (entries)
 constexpr uint32_t kListAllMax = 8192;       // tensors up to this size list every non-zero key (no prediction)
 constexpr int kFinishRegs = 8;               // listed keys per thread the finish kernel can hold in registers
 constexpr uint32_t kCandLists = 64;          // sub-lists per tensor (plus one overflow list)
@@ -80,6 +80,8 @@ struct LayerDev {
   int32_t code, prev_code;
   uint32_t found_inf, curv_nonfinite;
   uint32_t sel_passes;     // passes over h beyond the EMA pass that the last probed step needed
+  uint32_t sel_listed;     // keys the EMA kernel listed at the last probed step
+  uint32_t sel_outcome;    // how the band check of the last probed step ended (see k_select_begin)
   // bookkeeping
   uint32_t applied_steps;  // steps that were not skipped
   uint32_t probes_seen;
@@ -87,9 +89,10 @@ struct LayerDev {
   // threshold selection
   uint32_t theta_key;      // |theta| bit pattern (scratch while a step selects, then the result)
   uint32_t theta_key_last; // theta of the previous probed step
+  uint32_t theta_key_last2;// theta of the probed step before that
   uint32_t n_theta;        // how many thresholds are known (0, 1, 2 = two or more)
-  uint32_t pred_center;    // key the window of this step was centred on
-  uint32_t pred_err;       // |theta - pred_center| of the last probed step
+  float var_hold;          // running mean squared error (keys^2) of predicting "same as last step"
+  float var_ext;           // same for the linear extrapolation from the last two steps
   uint32_t band_lo, band_hi;  // keys in [band_lo, band_hi) are listed by the EMA kernel
   uint32_t use_band;       // the EMA kernel writes the provisional mask and lists the band
   uint32_t mask_done;      // the mask needs no separate pass this step

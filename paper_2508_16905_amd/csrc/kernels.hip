@@ -635,6 +635,15 @@ __global__ __launch_bounds__(kThreads) void k_select_begin(const TensorDesc* __r
   else outcome = 2;
   if (outcome != 0) reset_cand_counters(counters, l);  // drop whatever the EMA kernel listed
   if (threadIdx.x != 0) return;
+  // diagnostic: 0 small tensor, 1 band held, 2 no band this step, 3 threshold above the band,
+  // 4 threshold below the band, 5 too many keys listed, 6 fewer non-zero keys than k
+  ls.sel_listed = listed;
+  ls.sel_outcome = td.list_all ? 0u
+                   : k > nonzero ? 6u
+                   : !ls.use_band ? 2u
+                   : above >= k ? 3u
+                   : k > above + listed ? 4u
+                   : listed > td.cand_cap ? 5u : 1u;
   ls.acc_maxkey = maxkey;
   ls.acc_nonfinite = nonfin;
   ls.nonzero = nonzero;
@@ -789,8 +798,8 @@ __device__ __forceinline__ void mask_chunk(const TensorDesc& td, int64_t base, u
 // ---------------------------------------------------------------------------------------------
 // Finish: one workgroup per tensor resolves theta among the listed keys (radix select in LDS),
 // sets their mask bits, publishes theta / nnz and plans the next probed step: the band and the
-// fallback window are centred on the threshold extrapolated from the last two; their widths
-// follow the error the last predictions made.
+// fallback window are centred on the predicted threshold; their widths follow the error the
+// recent predictions made.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t abs_diff(uint32_t a, uint32_t b) { return a > b ? a - b : b - a; }
 
@@ -923,19 +932,41 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   ls.sel_passes = ls.passes - 1 + (ls.mask_done ? 0u : 1u);  // passes over h beyond the EMA pass
   ls.probes_seen = ls.probes_seen + 1;
   // ---- plan the next probed step ----
-  // error of this step's prediction (or, without one, the step-to-step change)
-  uint32_t err;
-  if (ls.predicted) err = abs_diff(theta, ls.pred_center);
-  else if (have >= 1) err = abs_diff(theta, prev);
-  else err = kUnknownPredErr;  // nothing known yet: about 1 % in value
-  if (ls.window_missed) err = max(err, kUnknownPredErr);
-  const uint32_t e = max(max(err, ls.pred_err), 16u);
-  ls.pred_err = err;
+  // Two predictors of the next threshold are tracked by the error each would have made for this
+  // step: "hold" (the last threshold; best when the threshold only jitters) and "extrapolate"
+  // (linear in key space from the last two; best while the curvature EMA is still drifting).
+  // Each keeps a running mean of its squared error (an error three times the running deviation
+  // replaces the mean at once); the predictor with the smaller one is used, and the band is a
+  // multiple of its deviation.
+  const uint32_t prev2 = ls.theta_key_last2;
+  const float unknown2 = (float)kUnknownPredErr * (float)kUnknownPredErr;
+  auto track = [](float var, float err, bool first) {
+    const float e2 = err * err;
+    if (first || e2 > 9.0f * var) return e2;
+    return 0.75f * var + 0.25f * e2;
+  };
+  float v_hold = unknown2, v_ext = 3.0e38f;
+  if (have >= 1) v_hold = track(ls.var_hold, (float)abs_diff(theta, prev), have < 2);
+  if (have >= 2) {
+    int64_t p = 2 * (int64_t)prev - (int64_t)prev2;
+    if (p < 0) p = 0;
+    v_ext = track(ls.var_ext, (float)abs_diff(theta, (uint32_t)p), !(ls.var_ext < 3.0e38f));
+  }
+  if (ls.window_missed) {
+    v_hold = fmaxf(v_hold, unknown2);
+    if (v_ext < 3.0e38f) v_ext = fmaxf(v_ext, unknown2);
+  }
+  ls.var_hold = v_hold;
+  ls.var_ext = v_ext;
+  ls.theta_key_last2 = prev;
   ls.theta_key_last = theta;
   ls.n_theta = have < 2 ? have + 1 : 2;
-  // centre: linear extrapolation in key space from the last two thresholds
+  const bool extrapolate = have >= 1 && v_ext < v_hold;
+  // e: 1.5 deviations of the chosen predictor (band = 3 e = 4.5 deviations, window half = 32 e)
+  const float dev = 1.5f * sqrtf(extrapolate ? v_ext : v_hold);
+  const uint32_t e = dev < 16.0f ? 16u : (dev > 1.0e9f ? 1000000000u : (uint32_t)dev);
   int64_t centre = (int64_t)theta;
-  if (have >= 1) centre += (int64_t)theta - (int64_t)prev;
+  if (extrapolate) centre += (int64_t)theta - (int64_t)prev;
   if (centre < 1) centre = 1;
   if (centre > 0x7f7fffff) centre = 0x7f7fffff;
   // fallback window: 2048 bins whose half (1024 bins) spans 32 e
@@ -943,8 +974,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   while (s < kFullShift && ((uint64_t)1024 << s) < (uint64_t)32 * e) ++s;
   const uint32_t cbin = (uint32_t)centre >> s;
   const uint32_t lo_bin = cbin > (uint32_t)(kHistBins / 2) ? cbin - kHistBins / 2 : 0u;
-  // band: 4 e on either side of the centre
-  const uint64_t half = (uint64_t)4 * e;
+  // band: 3 e on either side of the centre
+  const uint64_t half = (uint64_t)3 * e;
   const uint32_t band_lo = (uint64_t)centre > half ? (uint32_t)((uint64_t)centre - half) : 1u;
   const uint64_t hi64 = (uint64_t)centre + half + 1;
   const uint32_t band_hi = hi64 < 0x7f800000ull ? (uint32_t)hi64 : 0x7f800000u;
@@ -958,7 +989,6 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   ls.band_lo = band_lo;
   ls.band_hi = band_hi;
   ls.use_band = expect <= (uint64_t)(td.cand_cap - td.cand_cap / 4) ? 1u : 0u;
-  ls.pred_center = (uint32_t)centre;
   ls.predicted = 1;
   ls.window_missed = 0;
   ls.mask_done = 0;

@@ -135,11 +135,11 @@ typedef struct {
 #define TRIACCEL_N_STAGES 7
 #define TRIACCEL_PROFILE_RING 64
 typedef struct {
-  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + histogram + provisional mask
-                                  (+ first scan), 2 threshold refinement passes (fallback), 3 per-layer
-                                  assign, 4 update + cast of tensors whose storage size is unchanged
-                                  (+ fallback mask pass), 5 phased in-place update of tensors whose size
-                                  changes, 6 threshold resolution among listed keys + mask patch        */
+  float ms[TRIACCEL_N_STAGES]; /* 0 gradient statistics, 1 curvature EMA + provisional mask + band list,
+                                  2 per-layer kernel (band check, assign), 3 fallback radix select
+                                  (histogram passes), 4 update + cast of tensors whose storage size is
+                                  unchanged (+ fallback mask pass), 5 in-place update of tensors whose
+                                  size changes, 6 threshold resolution among listed keys + mask patch   */
 } triaccel_stage_times;
 
 /*

@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("TRIACCEL_LIBRARY") or os.path.join(_HERE, "libtriacce
 
 FP16, BF16, FP32 = 0, 1, 2
 N_STAGES = 7
-STAGE_NAMES = ("grad_stats", "curv_ema", "select_refine", "assign", "update", "update_resize", "select_finish")
+STAGE_NAMES = ("grad_stats", "curv_ema", "layer", "select_refine", "update", "update_resize", "select_finish")
 
 
 class Config(C.Structure):

@@ -321,21 +321,15 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   if (prof) TA_HIP(hipEventRecord(ev[0], s));
   TA_HIP(launch_grad_stats(T, sc, s));
   if (prof) TA_HIP(hipEventRecord(ev[1], s));
-  if (any_probe) {
-    TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, s));
-    TA_HIP(launch_select_begin(T, sc, h->cfg.sparsity_ppm, s));
-  }
+  if (any_probe) TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, s));
   if (prof) TA_HIP(hipEventRecord(ev[2], s));
-  if (any_probe) {
-    // fallback radix select; at most four rounds are ever needed: a predicted window that misses,
-    // then 11 + 11 + 9 key bits.  Idle (a few workgroups that exit) when the prediction held.
-    for (int round = 0; round < 4; ++round) {
-      TA_HIP(launch_hist_pass(T, sc, s));
-      TA_HIP(launch_select_scan(T, sc, s));
-    }
-  }
+  TA_HIP(launch_layer(T, sc, h->hp, s));
   if (prof) TA_HIP(hipEventRecord(ev[3], s));
-  TA_HIP(launch_assign(T, sc, h->hp, s));
+  if (any_probe) {
+    // fallback radix select: a predicted window that misses, then 11 + 11 + 9 key bits, is the
+    // most it can take; every launch leaves at once when no tensor is (still) in histogram mode
+    for (int round = 0; round < 4; ++round) TA_HIP(launch_hist_pass(T, sc, s));
+  }
   if (prof) TA_HIP(hipEventRecord(ev[4], s));
   TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
   if (prof) TA_HIP(hipEventRecord(ev[5], s));

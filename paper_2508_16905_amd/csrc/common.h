@@ -108,6 +108,7 @@ struct LayerDev {
   uint32_t nonzero;        // number of non-zero keys
   uint32_t dens_count, dens_width;  // key density near theta: dens_count keys per dens_width keys
   uint32_t count_above;    // the next histogram pass must count the keys above its window
+  uint32_t hist_arrived;   // chunks whose keys are in this round's histogram (cleared by the scan)
   // accumulators filled by atomics during a step and cleared by the kernel that consumes them
   uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite;
 };
@@ -117,6 +118,7 @@ struct GlobalDev {
   uint32_t skip_epoch;     // == step_id when the step must be skipped
   int32_t good_steps;      // consecutive applied steps since the last loss-scale change
   uint32_t trans_count[2]; // number of tensors whose storage size changes (double-buffered by step parity)
+  uint32_t hist_pending[2];// tensors still in histogram mode this step (same double buffering)
   // result record
   int32_t res_skipped;
   float res_next_scale;

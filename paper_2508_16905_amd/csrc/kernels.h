@@ -27,11 +27,9 @@ struct DeviceTables {
 
 hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
-hipError_t launch_select_begin(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s);
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
-hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
-hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
+hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
 hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
 hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s);

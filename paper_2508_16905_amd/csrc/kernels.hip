@@ -414,8 +414,8 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restr
 
 // ---------------------------------------------------------------------------------------------
 // Fallback: histogram pass over |h| for tensors whose threshold is not yet confined to a range
-// whose keys can be listed (mode kSelHist).  Persistent workgroups, each owning a contiguous
-// range of chunks so that the LDS histogram is flushed once per (workgroup, tensor); reads h only.
+// whose keys can be listed (mode kSelHist).  Workgroups own contiguous ranges of chunks so that
+// the LDS histogram is flushed once per (workgroup, tensor); reads h only.
 // ---------------------------------------------------------------------------------------------
 template <bool FULL>
 __device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, const Window& w, uint32_t* s_hist,
@@ -439,63 +439,6 @@ __device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, c
         else if (count_above) ++above;
       }
     }
-  }
-}
-
-__global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
-                                                        const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
-                                                        LayerDev* layers, const GlobalDev* glob, uint32_t* hist,
-                                                        StepScalars sc) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const uint32_t per = (total_chunks + gridDim.x - 1) / gridDim.x;
-  const uint32_t c0 = blockIdx.x * per;
-  const uint32_t c1 = min(c0 + per, total_chunks);
-  // nothing to do for this workgroup (the usual case: the prediction held): leave at once
-  bool any_active = false;
-  for (uint32_t c = c0; c < c1;) {
-    const uint32_t t = chunks[c].tensor;
-    const LayerDev& ls = layers[t];
-    any_active = any_active || (tds[t].has_probe != 0 && ls.mode == kSelHist && ls.passes > 0);
-    c = tds[t].first_chunk + tds[t].n_chunks;
-  }
-  if (!any_active) return;
-  __shared__ uint32_t s_hist[kHistBins];
-  for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
-  __syncthreads();
-  int cur = -1;
-  bool active = false;
-  Window w{0, 0, 0};
-  TensorDesc td;
-  bool count_above = false;  // the number of keys above the window is not known yet (predicted window)
-  uint32_t above = 0;
-  uint32_t c = c0;
-  while (c <= c1) {
-    const bool end = (c == c1);
-    const int t = end ? -2 : (int)chunks[c].tensor;
-    if (t != cur) {
-      if (cur >= 0 && active) {
-        flush_hist(s_hist, w.bins, hist + (size_t)cur * kHistBins);
-        above = wave_sum(above);
-        if ((threadIdx.x & (kWave - 1)) == 0 && above) atomicAdd(&layers[cur].acc_above, above);
-      }
-      if (end) break;
-      cur = t;
-      td = tds[t];
-      const LayerDev& ls = layers[t];
-      active = td.has_probe != 0 && ls.mode == kSelHist && ls.passes > 0;
-      w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
-      count_above = ls.count_above != 0;
-      above = 0;
-      if (!active) {
-        // jump over the rest of this tensor's chunks owned by this workgroup
-        c = min(td.first_chunk + td.n_chunks, c1);
-        continue;
-      }
-    }
-    const int64_t base = (int64_t)chunks[c].index * kChunk;
-    if (base + kChunk <= td.numel) hist_chunk<true>(td, base, w, s_hist, count_above, above);
-    else hist_chunk<false>(td, base, w, s_hist, count_above, above);
-    ++c;
   }
 }
 
@@ -578,20 +521,13 @@ __device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// First decision after the EMA pass, one workgroup per tensor: add up the per-chunk records and
-// decide whether the listed keys settle the threshold (band hit, or small tensor) or the tensor
-// must fall back to histogram passes.
+// First decision after the EMA pass (called by the per-layer kernel, one workgroup per tensor):
+// add up the per-chunk records and decide whether the listed keys settle the threshold (band
+// hit, or small tensor) or the tensor must fall back to histogram passes.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_select_begin(const TensorDesc* __restrict__ tds, LayerDev* layers,
-                                                           const GlobalDev* glob,
-                                                           const EmaPartial* __restrict__ ema_partials,
-                                                           uint32_t* counters, StepScalars sc,
-                                                           uint32_t sparsity_ppm) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const uint32_t l = blockIdx.x;
-  const TensorDesc td = tds[l];
-  if (!td.has_probe) return;
-  LayerDev& ls = layers[l];
+__device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob,
+                             const EmaPartial* __restrict__ ema_partials, uint32_t* counters, uint32_t step_id,
+                             uint32_t sparsity_ppm, uint32_t (*s_red)[kThreads / kWave]) {
   uint32_t above = 0, zeros = 0, maxkey = 0, nonfin = 0, listed = 0;
   for (uint32_t c = threadIdx.x; c < td.n_chunks; c += kThreads) {
     const EmaPartial p = ema_partials[td.first_chunk + c];
@@ -606,7 +542,6 @@ __global__ __launch_bounds__(kThreads) void k_select_begin(const TensorDesc* __r
   maxkey = wave_max(maxkey);
   nonfin = wave_or(nonfin);
   listed = wave_sum(listed);
-  __shared__ uint32_t s_red[5][kThreads / kWave];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   if (lane == 0) {
     s_red[0][wave] = above;
@@ -634,77 +569,72 @@ __global__ __launch_bounds__(kThreads) void k_select_begin(const TensorDesc* __r
   else if (ls.use_band && above < k && k <= above + listed && listed <= td.cand_cap) outcome = 0;
   else outcome = 2;
   if (outcome != 0) reset_cand_counters(counters, l);  // drop whatever the EMA kernel listed
-  if (threadIdx.x != 0) return;
-  // diagnostic: 0 small tensor, 1 band held, 2 no band this step, 3 threshold above the band,
-  // 4 threshold below the band, 5 too many keys listed, 6 fewer non-zero keys than k
-  ls.sel_listed = listed;
-  ls.sel_outcome = td.list_all ? 0u
-                   : k > nonzero ? 6u
-                   : !ls.use_band ? 2u
-                   : above >= k ? 3u
-                   : k > above + listed ? 4u
-                   : listed > td.cand_cap ? 5u : 1u;
-  ls.acc_maxkey = maxkey;
-  ls.acc_nonfinite = nonfin;
-  ls.nonzero = nonzero;
-  ls.k_rem = k;
-  ls.passes = 1;
-  ls.acc_above = 0;
-  if (outcome == 0) {
-    ls.mode = kSelCand;
-    ls.mask_done = 1;
-    if (td.list_all) {
-      ls.above = 0;
-      ls.rng_lo = 0;
-      ls.rng_hi = 0x80000000u;
+  if (threadIdx.x == 0) {
+    // diagnostic: 0 small tensor, 1 band held, 2 no band this step, 3 threshold above the band,
+    // 4 threshold below the band, 5 too many keys listed, 6 fewer non-zero keys than k
+    ls.sel_listed = listed;
+    ls.sel_outcome = td.list_all ? 0u
+                     : k > nonzero ? 6u
+                     : !ls.use_band ? 2u
+                     : above >= k ? 3u
+                     : k > above + listed ? 4u
+                     : listed > td.cand_cap ? 5u : 1u;
+    ls.acc_maxkey = maxkey;
+    ls.acc_nonfinite = nonfin;
+    ls.nonzero = nonzero;
+    ls.k_rem = k;
+    ls.passes = 1;
+    ls.acc_above = 0;
+    if (outcome == 0) {
+      ls.mode = kSelCand;
+      ls.mask_done = 1;
+      if (td.list_all) {
+        ls.above = 0;
+        ls.rng_lo = 0;
+        ls.rng_hi = 0x80000000u;
+      } else {
+        ls.above = above;
+        ls.rng_lo = ls.band_lo;
+        ls.rng_hi = ls.band_hi;
+        ls.dens_count = listed;
+        ls.dens_width = ls.band_hi - ls.band_lo;
+      }
+    } else if (outcome == 1) {
+      ls.mode = kSelExact;
+      ls.mask_done = 0;
+      ls.theta_key = 0;
+      ls.above = nonzero;
+      ls.sel_count = 0;
     } else {
-      ls.above = above;
-      ls.rng_lo = ls.band_lo;
-      ls.rng_hi = ls.band_hi;
-      ls.dens_count = listed;
-      ls.dens_width = ls.band_hi - ls.band_lo;
-    }
-  } else if (outcome == 1) {
-    ls.mode = kSelExact;
-    ls.mask_done = 0;
-    ls.theta_key = 0;
-    ls.above = nonzero;
-    ls.sel_count = 0;
-  } else {
-    // histogram over the predicted window if there is one, else over the full key range
-    ls.mode = kSelHist;
-    ls.mask_done = 0;
-    ls.above = 0;
-    ls.count_above = ls.predicted;
-    if (!ls.predicted) {
-      ls.win_lo = 0;
-      ls.win_shift = kFullShift;
-      ls.win_bins = kHistBins;
+      // histogram over the predicted window if there is one, else over the full key range
+      ls.mode = kSelHist;
+      ls.mask_done = 0;
+      ls.above = 0;
+      ls.count_above = ls.predicted;
+      if (!ls.predicted) {
+        ls.win_lo = 0;
+        ls.win_shift = kFullShift;
+        ls.win_bins = kHistBins;
+      }
+      atomicAdd(&glob->hist_pending[step_id & 1u], 1u);
     }
   }
+  __syncthreads();
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scan after a histogram pass: one workgroup per tensor reads the tensor's histogram, clears it,
-// and decides whether theta is now exact, lies in a range whose keys can be listed by the mask
-// pass, or needs a finer histogram.
+// Scan after a histogram pass, by one workgroup for one tensor in mode kSelHist: read the
+// tensor's histogram, clear it, and decide whether theta is now exact, lies in a range whose keys
+// can be listed by the mask pass, or needs a finer histogram.  Uniform over the workgroup.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __restrict__ tds, LayerDev* layers,
-                                                          const GlobalDev* glob, uint32_t* hist, StepScalars sc) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const uint32_t l = blockIdx.x;
-  const TensorDesc td = tds[l];
-  if (!td.has_probe) return;
-  LayerDev& ls = layers[l];
-  if (ls.mode != kSelHist || ls.passes == 0) return;
-  __shared__ uint32_t s_hist[kHistBins];
-  __shared__ uint32_t s_part[kThreads];
-  __shared__ uint32_t s_out[8];
+__device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob, uint32_t* hist,
+                            uint32_t step_id, uint32_t* s_hist, uint32_t* s_part, uint32_t* s_out) {
   const uint32_t bins = ls.win_bins, lo = ls.win_lo, shift = ls.win_shift;
   uint32_t* gh = hist + (size_t)l * kHistBins;
   uint32_t local = 0;
   for (uint32_t b = threadIdx.x; b < kHistBins; b += kThreads) {
-    const uint32_t v = (b < bins) ? gh[b] : 0u;
+    // counted by other workgroups of the running kernel: read at device scope
+    const uint32_t v = (b < bins) ? __hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     s_hist[b] = v;
     local += v;
     if (v) gh[b] = 0;
@@ -715,43 +645,124 @@ __global__ __launch_bounds__(kThreads) void k_select_scan(const TensorDesc* __re
   const uint32_t in_window = s_part[0] + s_part[1] + s_part[2] + s_part[3];
   __syncthreads();
   const uint32_t k = ls.k_rem;
-  const uint32_t above = ls.count_above ? ls.acc_above : ls.above;  // counted by this pass, or known
-  // the window (a predicted one) does not contain theta: restart with the full key range
-  if (above >= k || above + in_window < k) {
-    if (threadIdx.x == 0) {
+  // counted by this pass (same remark), or known
+  const uint32_t above = ls.count_above ? __hip_atomic_load(&ls.acc_above, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ls.above;
+  const bool missed = above >= k || above + in_window < k;
+  BinHit hit{0, 0, 0};
+  if (!missed) hit = find_rank_from_top<kThreads>(s_hist, bins, k - above, s_part, s_out);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ls.acc_above = 0;
+    ls.count_above = 0;
+    ls.hist_arrived = 0;
+    ls.passes = ls.passes + 1;
+    if (missed) {
+      // the window (a predicted one) does not contain theta: restart with the full key range
       ls.win_lo = 0;
       ls.win_shift = kFullShift;
       ls.win_bins = kHistBins;
       ls.above = 0;
-      ls.acc_above = 0;
-      ls.count_above = 0;
-      ls.passes = ls.passes + 1;
       ls.window_missed = 1;
+    } else {
+      const uint32_t new_lo = lo + (hit.bin << shift);
+      ls.above = above + hit.higher;
+      ls.sel_count = hit.count;
+      ls.dens_count = hit.count;
+      ls.dens_width = 1u << shift;
+      if (shift == 0) {
+        ls.mode = kSelExact;
+        ls.theta_key = new_lo;
+        atomicSub(&glob->hist_pending[step_id & 1u], 1u);
+      } else if (hit.count <= td.cand_cap) {
+        ls.mode = kSelCand;
+        ls.rng_lo = new_lo;
+        ls.rng_hi = new_lo + (1u << shift);
+        atomicSub(&glob->hist_pending[step_id & 1u], 1u);
+      } else {
+        const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
+        ls.win_lo = new_lo;
+        ls.win_shift = ns;
+        ls.win_bins = 1u << (shift - ns);
+      }
     }
-    return;
   }
-  const BinHit hit = find_rank_from_top<kThreads>(s_hist, bins, k - above, s_part, s_out);
-  if (threadIdx.x != 0) return;
-  const uint32_t new_lo = lo + (hit.bin << shift);
-  ls.above = above + hit.higher;
-  ls.acc_above = 0;
-  ls.count_above = 0;
-  ls.sel_count = hit.count;
-  ls.dens_count = hit.count;
-  ls.dens_width = 1u << shift;
-  ls.passes = ls.passes + 1;
-  if (shift == 0) {
-    ls.mode = kSelExact;
-    ls.theta_key = new_lo;
-  } else if (hit.count <= td.cand_cap) {
-    ls.mode = kSelCand;
-    ls.rng_lo = new_lo;
-    ls.rng_hi = new_lo + (1u << shift);
-  } else {
-    const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
-    ls.win_lo = new_lo;
-    ls.win_shift = ns;
-    ls.win_bins = 1u << (shift - ns);
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
+// One fallback round: histogram pass over the tensors in histogram mode, each workgroup over its
+// share of the chunk list.  The workgroup that is the last to deliver its part of a tensor's
+// histogram also scans it (select_scan), so a round is one launch and no workgroup ever waits
+// for another.  Leaves at once when no tensor is in histogram mode: a workgroup that sees the
+// pending count at zero owns no chunk of a tensor still being counted, because a tensor's scan,
+// which alone lowers the count, needs every workgroup owning one of its chunks to have arrived.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
+                                                        const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
+                                                        LayerDev* layers, GlobalDev* glob, uint32_t* hist,
+                                                        StepScalars sc) {
+  if (step_skipped(glob, sc.step_id)) return;
+  if (__hip_atomic_load(&glob->hist_pending[sc.step_id & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+  __shared__ uint32_t s_hist[kHistBins];
+  __shared__ uint32_t s_part[kThreads];
+  __shared__ uint32_t s_out[8];
+  __shared__ uint32_t s_last;
+  for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+  __syncthreads();
+  const uint32_t per = (total_chunks + gridDim.x - 1) / gridDim.x;
+  const uint32_t c0 = min(blockIdx.x * per, total_chunks);
+  const uint32_t c1 = min(c0 + per, total_chunks);
+  int cur = -1;
+  bool active = false;
+  Window w{0, 0, 0};
+  TensorDesc td;
+  bool count_above = false;  // the number of keys above the window is not known yet (predicted window)
+  uint32_t above = 0;
+  uint32_t mine = 0;         // chunks of the current tensor counted by this workgroup
+  uint32_t c = c0;
+  while (c <= c1) {
+    const bool end = (c == c1);
+    const int t = end ? -2 : (int)chunks[c].tensor;
+    if (t != cur) {
+      if (cur >= 0 && active) {
+        flush_hist(s_hist, w.bins, hist + (size_t)cur * kHistBins);
+        above = wave_sum(above);
+        if ((threadIdx.x & (kWave - 1)) == 0 && above) atomicAdd(&layers[cur].acc_above, above);
+        // release: this workgroup's atomics are complete before its arrival is counted
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          const uint32_t before = atomicAdd(&layers[cur].hist_arrived, mine);
+          s_last = (before + mine == td.n_chunks) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (s_last) {
+          __threadfence();  // acquire: the scan below reads what the other workgroups added
+          select_scan((uint32_t)cur, td, layers[cur], glob, hist, sc.step_id, s_hist, s_part, s_out);
+          for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+          __syncthreads();
+        }
+      }
+      if (end) break;
+      cur = t;
+      td = tds[t];
+      const LayerDev& ls = layers[t];
+      active = td.has_probe != 0 && ls.mode == kSelHist && ls.passes > 0;
+      w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
+      count_above = ls.count_above != 0;
+      above = 0;
+      mine = 0;
+      if (!active) {
+        // jump over the rest of this tensor's chunks owned by this workgroup
+        c = min(td.first_chunk + td.n_chunks, c1);
+        continue;
+      }
+    }
+    const int64_t base = (int64_t)chunks[c].index * kChunk;
+    if (base + kChunk <= td.numel) hist_chunk<true>(td, base, w, s_hist, count_above, above);
+    else hist_chunk<false>(td, base, w, s_hist, count_above, above);
+    ++mine;
+    ++c;
   }
 }
 
@@ -1003,19 +1014,23 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 4: per-layer assignment (one workgroup per tensor): merge the chunk moments, variance
+// Stage 4: per-layer kernel (one workgroup per tensor): band check of the threshold selection
+// (select_begin above), then the per-layer assignment: merge the chunk moments, variance
 // EMA (Sec. 3.1 first equation), precision rule (second equation) with curvature promotion
 // (Sec. 3.2), step size eta_l (Sec. 3.2), overflow decision and loss-scale schedule.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_assign(const TensorDesc* __restrict__ tds,
-                                                     const StatPartial* __restrict__ partials, LayerDev* layers,
-                                                     GlobalDev* glob, uint32_t* trans_list, uint32_t n_tensors,
-                                                     StepScalars sc, Hyper hp) {
+__global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict__ tds,
+                                                    const StatPartial* __restrict__ partials,
+                                                    const EmaPartial* __restrict__ ema_partials, uint32_t* counters,
+                                                    LayerDev* layers, GlobalDev* glob, uint32_t* trans_list,
+                                                    uint32_t n_tensors, StepScalars sc, Hyper hp) {
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
   LayerDev& ls = layers[l];
   const bool skip = step_skipped(glob, sc.step_id);
   __shared__ Moments s_m[kThreads / kWave];
+  __shared__ uint32_t s_red[5][kThreads / kWave];
+  if (!skip && td.has_probe) select_begin(l, td, ls, glob, ema_partials, counters, sc.step_id, hp.sparsity_ppm, s_red);
   Moments mom{0.0, 0.0, 0.0};
   if (!skip) {
     // fixed merge order: each thread folds a contiguous run of chunk partials, then a tree
@@ -1070,6 +1085,7 @@ __global__ __launch_bounds__(kThreads) void k_assign(const TensorDesc* __restric
   }
   if (l == 0) {
     glob->trans_count[(sc.step_id + 1u) & 1u] = 0;
+    glob->hist_pending[(sc.step_id + 1u) & 1u] = 0;
     float next = sc.loss_scale;
     if (skip) {
       glob->good_steps = 0;
@@ -1278,23 +1294,10 @@ hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float b
   return hipSuccess;
 }
 
-hipError_t launch_select_begin(const DeviceTables& t, const StepScalars& sc, uint32_t sparsity_ppm, hipStream_t s) {
-  hipLaunchKernelGGL(k_select_begin, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                     t.ema_partials, t.cand_counters, sc, sparsity_ppm);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
   const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_hist_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
                      t.glob, t.hist, sc);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
-hipError_t launch_select_scan(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
-  hipLaunchKernelGGL(k_select_scan, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.hist, sc);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -1306,9 +1309,9 @@ hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hi
   return hipSuccess;
 }
 
-hipError_t launch_assign(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s) {
-  hipLaunchKernelGGL(k_assign, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.partials, t.layers, t.glob,
-                     t.trans_list, t.n_tensors, sc, hp);
+hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s) {
+  hipLaunchKernelGGL(k_layer, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.partials, t.ema_partials,
+                     t.cand_counters, t.layers, t.glob, t.trans_list, t.n_tensors, sc, hp);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

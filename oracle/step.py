@@ -40,6 +40,8 @@ class OracleConfig:
     delta_down: int = 16
     b_min: int = 16
     b_max: int = 4096
+    lambda_source: int = 0       # lambda_l of Sec. 3.2: 0 = largest kept |h_i| of the diagonal EMA,
+                                 # 1 = largest |Rayleigh quotient| of the latched power iteration
 
     @classmethod
     def from_hyper(cls, hyper: dict) -> "OracleConfig":
@@ -72,6 +74,12 @@ class OracleTensor:
         self.found_inf = 0
         self.curv_nonfinite = 0
         self.probes_seen = 0
+        # power iteration (Sec. 3.2, third equation)
+        self.rayleigh = np.zeros(0, dtype=np.float32)
+        self.resid = np.zeros(0, dtype=np.float32)
+        self.hnorm = np.zeros(0, dtype=np.float32)
+        self.deficient = 0
+        self.lam_power = np.float32(0)
 
     def param_view(self) -> np.ndarray:
         """The stored parameters in their current dtype (uint16 bit patterns for 2-byte codes)."""
@@ -131,6 +139,8 @@ class OracleTriAccel:
             L.oracle_threshold_mask(t.curv.ctypes.data, t.numel, cfg.sparsity_ppm, t.mask.ctypes.data,
                                     C.byref(theta), C.byref(nnz), C.byref(lam))
             t.theta, t.nnz, t.lam = f32(theta.value), int(nnz.value), f32(lam.value)
+        if cfg.lambda_source == 1:
+            t.lam = t.lam_power
         # (2) precision allocation, (3) per-layer learning rate
         t.prev_code = t.code
         if control_step:
@@ -142,6 +152,25 @@ class OracleTriAccel:
         L.oracle_update(t.buf.ctypes.data, t.prev_code, t.code, g.ctypes.data, t.grad_dtype,
                         None if t.mom is None else t.mom.ctypes.data, t.numel, inv_scale,
                         f32(cfg.weight_decay), f32(cfg.momentum), t.eta)
+
+    def power_step(self, us: Sequence[np.ndarray], hus: Sequence[np.ndarray], k: int, latch: bool) -> None:
+        """One power iteration (Sec. 3.2) per tensor on k supplied pairs (u_j, H u_j); ``us[l]`` and
+        ``hus[l]`` are fp32 arrays of shape (k, numel).  The new vectors overwrite ``us[l]``.  With
+        ``latch`` the layer's lambda for the following steps becomes max_j |rayleigh_j|."""
+        L = lib()
+        for t, u, hu in zip(self.tensors, us, hus):
+            assert u.dtype == np.float32 and hu.dtype == np.float32 and u.size == k * t.numel == hu.size
+            ray, res, hn = (np.zeros(k, dtype=np.float64) for _ in range(3))
+            deficient = C.c_uint32(0)
+            out = np.empty(k * t.numel, dtype=np.float32)
+            L.oracle_power_step(u.ctypes.data, hu.ctypes.data, out.ctypes.data, t.numel, int(k),
+                                ray.ctypes.data_as(C.POINTER(C.c_double)), res.ctypes.data_as(C.POINTER(C.c_double)),
+                                hn.ctypes.data_as(C.POINTER(C.c_double)), C.byref(deficient))
+            u.reshape(-1)[:] = out
+            t.rayleigh, t.resid, t.hnorm = ray.astype(np.float32), res.astype(np.float32), hn.astype(np.float32)
+            t.deficient = int(deficient.value)
+            if latch:
+                t.lam_power = np.float32(np.max(np.abs(ray)))
 
     def step(self, grads: Sequence[np.ndarray], zs: Sequence[Optional[np.ndarray]],
              hzs: Sequence[Optional[np.ndarray]], lr: float, loss_scale: float, batch_size: int,

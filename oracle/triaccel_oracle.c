@@ -314,24 +314,66 @@ int32_t oracle_batch_next(int32_t batch, uint64_t mem_used, uint64_t mem_total,
 }
 
 /* ------------------------------------------------------------------------ */
-/* Power iteration of Sec. 3.2 (third equation) on a supplied pair (u, Hu):
- *   rayleigh = u^T H u / u^T u,   norm = ||H u||_2,   u_next = H u / ||H u||.
- * Sums in double.                                                            */
+/* Power iteration of Sec. 3.2 (third equation) for the top-k eigenvalues, one
+ * iteration on k supplied pairs (u_j, H u_j), j = 0..k-1, vector j stored at
+ * offset j*n:
+ *   rayleigh_j = u_j^T (H u_j) / u_j^T u_j                      (the printed quotient)
+ *   resid_j    = || H u_j - rayleigh_j u_j || / || u_j ||        (convergence measure)
+ *   hnorm_j    = || H u_j ||
+ *   v_j = H u_j - sum_{i<j} (q_i^T v_j) q_i     in order i = 0..j-1 (modified Gram-Schmidt)
+ *   q_j = v_j / || v_j ||,   u_j <- q_j
+ * For k = 1 this is the printed iteration u <- H u / ||H u|| literally; for k > 1 the earlier
+ * directions are projected out before normalising, which is what makes vector j converge to
+ * the j-th eigenvector (the paper asks for the top k but prints the single-vector form only).
+ * A vector whose remainder is numerically nothing, ||v_j||^2 <= 1e-12 ||H u_j||^2, has no
+ * direction left: q_j = 0 and bit j of *deficient is set.  A zero iterate (u_j^T u_j = 0) has
+ * no quotient: rayleigh_j = resid_j = 0.
+ * Everything in double; the new vectors are rounded to fp32 once.            */
 /* ------------------------------------------------------------------------ */
-void oracle_power_iter(const float *u, const float *hu, float *u_next, int64_t n,
-                       double *rayleigh_out, double *norm_out)
+void oracle_power_step(const float *u, const float *hu, float *u_next, int64_t n, int32_t k,
+                       double *rayleigh, double *resid, double *hnorm, uint32_t *deficient)
 {
-    double uhu = 0.0, uu = 0.0, hh = 0.0;
-    for (int64_t i = 0; i < n; ++i) {
-        uhu += (double)u[i] * (double)hu[i];
-        uu += (double)u[i] * (double)u[i];
-        hh += (double)hu[i] * (double)hu[i];
+    double *q = (double *)malloc((size_t)k * (size_t)n * sizeof(double));
+    uint32_t def = 0;
+    for (int32_t j = 0; j < k; ++j) {
+        const float *uj = u + (int64_t)j * n, *wj = hu + (int64_t)j * n;
+        double uw = 0.0, uu = 0.0, ww = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            uw += (double)uj[i] * (double)wj[i];
+            uu += (double)uj[i] * (double)uj[i];
+            ww += (double)wj[i] * (double)wj[i];
+        }
+        double lam = 0.0, rr = 0.0;
+        if (uu > 0.0) {
+            lam = uw / uu;
+            for (int64_t i = 0; i < n; ++i) {
+                double d = (double)wj[i] - lam * (double)uj[i];
+                rr += d * d;
+            }
+            rr = sqrt(rr) / sqrt(uu);
+        }
+        rayleigh[j] = lam;
+        resid[j] = rr;
+        hnorm[j] = sqrt(ww);
+        double *v = q + (int64_t)j * n;
+        for (int64_t i = 0; i < n; ++i) v[i] = (double)wj[i];
+        for (int32_t p = 0; p < j; ++p) {
+            const double *qp = q + (int64_t)p * n;
+            double dot = 0.0;
+            for (int64_t i = 0; i < n; ++i) dot += qp[i] * v[i];
+            for (int64_t i = 0; i < n; ++i) v[i] -= dot * qp[i];
+        }
+        double vv = 0.0;
+        for (int64_t i = 0; i < n; ++i) vv += v[i] * v[i];
+        if (vv <= 1e-12 * ww) {
+            def |= 1u << j;
+            for (int64_t i = 0; i < n; ++i) v[i] = 0.0;
+        } else {
+            double nv = sqrt(vv);
+            for (int64_t i = 0; i < n; ++i) v[i] = v[i] / nv;
+        }
+        for (int64_t i = 0; i < n; ++i) u_next[(int64_t)j * n + i] = (float)v[i];
     }
-    double norm = sqrt(hh);
-    *rayleigh_out = uhu / uu;
-    *norm_out = norm;
-    if (u_next) {
-        float inv = (float)(1.0 / norm);
-        for (int64_t i = 0; i < n; ++i) u_next[i] = hu[i] * inv;
-    }
+    *deficient = def;
+    free(q);
 }

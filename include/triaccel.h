@@ -73,6 +73,11 @@ typedef struct {
   double rho_low, rho_high;     /* memory utilisation thresholds (Sec. 3.3)                         */
   int32_t delta_up, delta_down; /* batch-size steps (Sec. 3.3)                                      */
   int32_t b_min, b_max;         /* clamp of the batch size                                          */
+  int32_t power_k;         /* vectors per layer that triaccel_power_iter may be called with (top-k
+                              eigenvalues, Sec. 3.2 / 4.1: k = 5); 0 = no workspace for it; <= 8      */
+  int32_t lambda_source;   /* lambda_l of the step-size and promotion rules (Sec. 3.2):
+                              0 = largest kept |h_i| of the diagonal curvature EMA,
+                              1 = max_j |Rayleigh quotient| latched by triaccel_power_iter            */
 } triaccel_config;
 
 /* One parameter tensor.  Contiguous, flat; numel elements. */
@@ -185,6 +190,43 @@ int triaccel_set_profiling(triaccel_handle h, int32_t on);
  * (0 = the last one; at most TRIACCEL_PROFILE_RING - 1).  That step must have run with profiling on.
  */
 int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_stage_times *out);
+
+/*
+ * Power iteration for the top-k eigenvalues of each layer's Hessian (Sec. 3.2, third equation:
+ * u <- H u / ||H u||, lambda ~ u^T H u / u^T u).  The caller owns the Hessian-vector products; one
+ * call performs one iteration on k vectors per layer.  On entry u holds the current vectors u_j and
+ * hu the products H_l u_j; on return (stream order) u_j holds the normalised H_l u_j with the
+ * directions j' < j projected out first (ordered Gram-Schmidt: for k = 1 exactly the printed
+ * iteration; for k > 1 vector j converges to the j-th eigenvector), and the per-layer record holds
+ *   rayleigh_j = u_j . H u_j / u_j . u_j,   hnorm_j = ||H u_j||,
+ *   resid_j = ||H u_j - rayleigh_j u_j|| / ||u_j||   (convergence measure).
+ * A vector with no direction left (remainder <= 1e-6 of ||H u_j||) is set to zero and flagged.
+ */
+typedef struct {
+  float *u;         /* device; fp32; vector j occupies elements [j*stride, j*stride + numel); in/out   */
+  const float *hu;  /* device; fp32; same layout; read only                                            */
+  int64_t stride;   /* elements between consecutive vectors: >= numel and a multiple of 4              */
+} triaccel_power_tensor;
+
+typedef struct {
+  float rayleigh[8]; /* entries j >= k of the last call are 0                                           */
+  float resid[8];
+  float hnorm[8];
+  uint32_t deficient; /* bit j: vector j had no direction left and was zeroed                           */
+  float lambda_max;   /* max_j |rayleigh_j| of the last call                                            */
+  float lambda_latched; /* the value triaccel_step uses when lambda_source == 1 (0 before any latch)    */
+} triaccel_power_info;
+
+/*
+ * Enqueue one iteration.  n must equal the n of triaccel_init (numel per tensor as given there);
+ * 1 <= k <= config.power_k.  latch != 0: lambda_l <- max_j |rayleigh_j| of this call, used by the
+ * following triaccel_step calls when config.lambda_source == 1.  Asynchronous.
+ */
+int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor *vectors, int32_t n, int32_t k,
+                        int32_t latch);
+
+/* Wait for the stream and copy the n per-layer records of the last triaccel_power_iter call. */
+int triaccel_power_state(triaccel_handle h, triaccel_power_info *out, int32_t n);
 
 /*
  * Utility: convert n fp32 values (device) to `dtype` (device) with the same round-to-nearest-even

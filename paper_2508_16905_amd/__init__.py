@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     STAGE_NAMES,
     Config,
     LayerInfo,
+    PowerInfo,
+    PowerTensor,
     StepArgs,
     StepResult,
     Tensor,
@@ -22,6 +24,8 @@ from .binding import (  # noqa: F401
     triaccel_destroy,
     triaccel_init,
     triaccel_layer_state,
+    triaccel_power_iter,
+    triaccel_power_state,
     triaccel_result,
     triaccel_set_profiling,
     triaccel_stage_times_get,

@@ -42,14 +42,18 @@ class Config(C.Structure):
         ("delta_down", C.c_int32),
         ("b_min", C.c_int32),
         ("b_max", C.c_int32),
+        ("power_k", C.c_int32),
+        ("lambda_source", C.c_int32),
     ]
+    # fields a hyper-parameter dict may leave out
+    _OPTIONAL = {"power_k": 0, "lambda_source": 0}
 
     @classmethod
     def from_hyper(cls, hyper: dict) -> "Config":
         cfg = cls()
         cfg.struct_size = C.sizeof(cls)
         for name, _ in cls._fields_[1:]:
-            setattr(cfg, name, hyper[name])
+            setattr(cfg, name, hyper[name] if name in hyper else cls._OPTIONAL[name])
         return cfg
 
 
@@ -110,6 +114,21 @@ class LayerInfo(C.Structure):
     ]
 
 
+class PowerTensor(C.Structure):
+    _fields_ = [("u", C.c_void_p), ("hu", C.c_void_p), ("stride", C.c_int64)]
+
+
+class PowerInfo(C.Structure):
+    _fields_ = [
+        ("rayleigh", C.c_float * 8),
+        ("resid", C.c_float * 8),
+        ("hnorm", C.c_float * 8),
+        ("deficient", C.c_uint32),
+        ("lambda_max", C.c_float),
+        ("lambda_latched", C.c_float),
+    ]
+
+
 class StageTimes(C.Structure):
     _fields_ = [("ms", C.c_float * N_STAGES)]
 
@@ -126,6 +145,8 @@ EXPORTS = {
     "triaccel_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "triaccel_stage_times_get": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(StageTimes)]),
     "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
+    "triaccel_power_iter": (C.c_int, [C.c_void_p, C.POINTER(PowerTensor), C.c_int32, C.c_int32, C.c_int32]),
+    "triaccel_power_state": (C.c_int, [C.c_void_p, C.POINTER(PowerInfo), C.c_int32]),
 }
 
 _lib: Optional[C.CDLL] = None
@@ -225,3 +246,15 @@ def triaccel_stage_times_get(handle, steps_back: int = 0):
 def triaccel_cast_f32(src_ptr: int, dst_ptr: int, n: int, dtype: int, stream: int = 0) -> None:
     _check(load_library().triaccel_cast_f32(C.c_void_p(src_ptr), C.c_void_p(dst_ptr), n, dtype, C.c_void_p(stream)),
            "triaccel_cast_f32")
+
+
+def triaccel_power_iter(handle, vectors, k: int, latch: bool) -> None:
+    """``vectors`` is a ctypes array ``(PowerTensor * n)`` or a sequence of ``PowerTensor``."""
+    arr = vectors if isinstance(vectors, C.Array) else (PowerTensor * len(vectors))(*vectors)
+    _check(load_library().triaccel_power_iter(handle, arr, len(arr), k, int(latch)), "triaccel_power_iter")
+
+
+def triaccel_power_state(handle, n: int):
+    arr = (PowerInfo * n)()
+    _check(load_library().triaccel_power_state(handle, arr, n), "triaccel_power_state")
+    return arr

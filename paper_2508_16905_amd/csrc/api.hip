@@ -13,6 +13,7 @@
 
 #include "../../include/triaccel.h"
 #include "kernels.h"
+#include "power.h"
 
 using namespace triaccel;
 
@@ -62,6 +63,14 @@ struct triaccel_ctx {
   uint64_t ev_step[TRIACCEL_PROFILE_RING] = {};  // step_index recorded in each ring slot (0 = none)
   std::vector<LayerDev> layer_host;
   std::vector<void*> device_allocs;
+  // power iteration (only with cfg.power_k > 0)
+  PowerTables pt{};
+  PowerDesc* power_staging[kRing] = {};
+  hipEvent_t power_ev[kRing] = {};
+  bool power_used[kRing] = {};
+  int power_pos = 0;
+  bool power_called = false;
+  std::vector<PowerLayer> power_host;
 };
 
 namespace {
@@ -96,6 +105,9 @@ int validate_config(const triaccel_config* cfg) {
   if (!(cfg->scale_backoff > 0.0f && cfg->scale_backoff <= 1.0f) || !(cfg->scale_growth >= 1.0f)) return TRIACCEL_E_INVALID_ARG;
   if (!(cfg->rho_low >= 0.0 && cfg->rho_low <= cfg->rho_high && cfg->rho_high <= 1.0)) return TRIACCEL_E_INVALID_ARG;
   if (cfg->delta_up < 0 || cfg->delta_down < 0 || cfg->b_min < 1 || cfg->b_max < cfg->b_min) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->power_k < 0 || cfg->power_k > kMaxPowerK) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->lambda_source != 0 && cfg->lambda_source != 1) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->lambda_source == 1 && cfg->power_k == 0) return TRIACCEL_E_INVALID_ARG;
   return TRIACCEL_OK;
 }
 
@@ -118,6 +130,8 @@ void free_ctx(triaccel_ctx* c) {
   for (int i = 0; i < kRing; ++i) {
     if (c->staging[i]) (void)hipHostFree(c->staging[i]);
     if (c->staging_ev[i]) (void)hipEventDestroy(c->staging_ev[i]);
+    if (c->power_staging[i]) (void)hipHostFree(c->power_staging[i]);
+    if (c->power_ev[i]) (void)hipEventDestroy(c->power_ev[i]);
   }
   if (c->pinned_res) (void)hipHostFree(c->pinned_res);
   for (auto& set : c->ev)
@@ -167,7 +181,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   c->hp = Hyper{config->beta_var,     config->beta_curv,     config->tau_low,       config->tau_high,
                 config->tau_curv,     config->alpha,         config->sparsity_ppm,  config->momentum,
                 config->weight_decay, config->ctrl_interval, config->scale_backoff, config->scale_growth,
-                config->growth_interval};
+                config->growth_interval, config->lambda_source};
   auto fail = [&](int code) {
     free_ctx(c);
     return code;
@@ -233,6 +247,9 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   if ((rc = dev_alloc(c, &T.trans_list, (size_t)n * 2))) return fail(rc);
   e = hipMemcpy(T.chunks, chunks.data(), chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(chunks)"));
+  // shapes and chunk ranges are valid from now on; the pointers arrive with every step
+  e = hipMemcpy(T.tensors, c->desc.data(), (size_t)n * sizeof(TensorDesc), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(tensor table)"));
   e = hipMemcpy(T.layers, c->layer_host.data(), (size_t)n * sizeof(LayerDev), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(layers)"));
   for (int i = 0; i < kRing; ++i) {
@@ -240,6 +257,39 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
     if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(staging)"));
     e = hipEventCreateWithFlags(&c->staging_ev[i], hipEventDisableTiming);
     if (e != hipSuccess) return fail(hip_fail(e, "hipEventCreate"));
+  }
+  if (config->power_k > 0) {
+    // workspace of the power iteration: segment table, per-segment sums, per-layer records
+    std::vector<SegRef> segs;
+    std::vector<uint32_t> seg_first((size_t)n);
+    for (int32_t i = 0; i < n; ++i) {
+      seg_first[i] = (uint32_t)segs.size();
+      const uint32_t ns = (c->desc[i].n_chunks + kPowerSeg - 1) / kPowerSeg;
+      for (uint32_t k = 0; k < ns; ++k) segs.push_back(SegRef{(uint32_t)i, k});
+    }
+    PowerTables& P = c->pt;
+    P.tensors = T.tensors;
+    P.chunks = T.chunks;
+    P.layers = T.layers;
+    P.n_tensors = (uint32_t)n;
+    P.total_chunks = T.total_chunks;
+    P.total_segs = (uint32_t)segs.size();
+    if ((rc = dev_alloc(c, &P.descs, (size_t)n))) return fail(rc);
+    if ((rc = dev_alloc(c, &P.segs, segs.size()))) return fail(rc);
+    if ((rc = dev_alloc(c, &P.seg_first, (size_t)n))) return fail(rc);
+    if ((rc = dev_alloc(c, &P.partials, segs.size() * (size_t)power_partial_len(config->power_k)))) return fail(rc);
+    if ((rc = dev_alloc(c, &P.state, (size_t)n))) return fail(rc);
+    e = hipMemcpy(P.segs, segs.data(), segs.size() * sizeof(SegRef), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(segments)"));
+    e = hipMemcpy(P.seg_first, seg_first.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(segment index)"));
+    for (int i = 0; i < kRing; ++i) {
+      e = hipHostMalloc(reinterpret_cast<void**>(&c->power_staging[i]), (size_t)n * sizeof(PowerDesc), hipHostMallocDefault);
+      if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(power staging)"));
+      e = hipEventCreateWithFlags(&c->power_ev[i], hipEventDisableTiming);
+      if (e != hipSuccess) return fail(hip_fail(e, "hipEventCreate"));
+    }
+    c->power_host.resize((size_t)n);
   }
   e = hipHostMalloc(reinterpret_cast<void**>(&c->pinned_res), sizeof(GlobalDev), hipHostMallocDefault);
   if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(result)"));
@@ -384,6 +434,53 @@ int triaccel_layer_state(triaccel_handle h, triaccel_layer_info* out, int32_t n)
     o.sel_passes = ls.sel_passes;
     o.sel_listed = ls.sel_listed;
     o.sel_outcome = ls.sel_outcome;
+  }
+  return TRIACCEL_OK;
+}
+
+int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor* vectors, int32_t n, int32_t k, int32_t latch) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!vectors) return TRIACCEL_E_NULL_PTR;
+  if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
+  if (k < 1 || k > h->cfg.power_k) return TRIACCEL_E_INVALID_ARG;
+  for (int32_t i = 0; i < n; ++i) {
+    const triaccel_power_tensor& v = vectors[i];
+    if (!v.u || !v.hu) return TRIACCEL_E_NULL_PTR;
+    if (v.stride < h->numel[i] || (v.stride & 3) != 0) return TRIACCEL_E_INVALID_ARG;
+    if (!aligned16(v.u) || !aligned16(v.hu)) return TRIACCEL_E_ALIGNMENT;
+  }
+  const int slot = h->power_pos;
+  h->power_pos = (h->power_pos + 1) % kRing;
+  if (h->power_used[slot]) TA_HIP(hipEventSynchronize(h->power_ev[slot]));
+  for (int32_t i = 0; i < n; ++i) h->power_staging[slot][i] = PowerDesc{vectors[i].u, vectors[i].hu, vectors[i].stride};
+  TA_HIP(hipMemcpyAsync(h->pt.descs, h->power_staging[slot], (size_t)n * sizeof(PowerDesc), hipMemcpyHostToDevice,
+                        h->stream));
+  TA_HIP(hipEventRecord(h->power_ev[slot], h->stream));
+  h->power_used[slot] = true;
+  TA_HIP(launch_power_iter(h->pt, k, latch ? 1 : 0, h->stream));
+  h->power_called = true;
+  return TRIACCEL_OK;
+}
+
+int triaccel_power_state(triaccel_handle h, triaccel_power_info* out, int32_t n) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!out) return TRIACCEL_E_NULL_PTR;
+  if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
+  if (h->cfg.power_k == 0 || !h->power_called) return TRIACCEL_E_NOT_INITIALISED;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  TA_HIP(hipMemcpy(h->power_host.data(), h->pt.state, (size_t)n * sizeof(PowerLayer), hipMemcpyDeviceToHost));
+  TA_HIP(hipMemcpy(h->layer_host.data(), h->t.layers, (size_t)n * sizeof(LayerDev), hipMemcpyDeviceToHost));
+  for (int32_t i = 0; i < n; ++i) {
+    const PowerLayer& p = h->power_host[i];
+    triaccel_power_info& o = out[i];
+    for (int j = 0; j < kMaxPowerK; ++j) {
+      o.rayleigh[j] = p.rayleigh[j];
+      o.resid[j] = p.resid[j];
+      o.hnorm[j] = p.hnorm[j];
+    }
+    o.deficient = p.deficient;
+    o.lambda_max = p.lambda_max;
+    o.lambda_latched = h->layer_host[i].lambda_power;
   }
   return TRIACCEL_OK;
 }

@@ -40,6 +40,7 @@ struct Hyper {
   int32_t ctrl_interval;
   float scale_backoff, scale_growth;
   int32_t growth_interval;
+  int32_t lambda_source;  // 0: largest kept |h_i|; 1: latched power-iteration value
 };
 
 // Per-step scalars handed to the kernels.
@@ -81,7 +82,8 @@ struct LayerDev {
   uint32_t found_inf, curv_nonfinite;
   uint32_t sel_passes;     // passes over h beyond the EMA pass that the last probed step needed
   uint32_t sel_listed;     // keys the EMA kernel listed at the last probed step
-  uint32_t sel_outcome;    // how the band check of the last probed step ended (see k_select_begin)
+  uint32_t sel_outcome;    // how the band check of the last probed step ended (see select_begin)
+  float lambda_power;      // max_j |Rayleigh quotient| latched by the power iteration (Sec. 3.2)
   // bookkeeping
   uint32_t applied_steps;  // steps that were not skipped
   uint32_t probes_seen;

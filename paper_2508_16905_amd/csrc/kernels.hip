@@ -1066,6 +1066,7 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
     } else {
       ls.curv_nonfinite = 0;
     }
+    if (hp.lambda_source == 1) ls.lambda = ls.lambda_power;
     const int prev = ls.code;
     ls.prev_code = prev;
     int code = prev;

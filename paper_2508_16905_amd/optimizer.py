@@ -77,6 +77,22 @@ class TriAccel:
     def layer_state(self):
         return B.triaccel_layer_state(self.handle, self.n)
 
+    def power_iter(self, us: Sequence[torch.Tensor], hus: Sequence[torch.Tensor], k: int, latch: bool = False) -> None:
+        """Enqueue one power iteration (asynchronous).  ``us[i]`` and ``hus[i]`` are fp32 tensors of
+        shape (k, stride_i) with stride_i >= numel_i a multiple of 4; ``us[i]`` is overwritten."""
+        arr = (B.PowerTensor * self.n)()
+        for i in range(self.n):
+            assert us[i].dtype == torch.float32 and hus[i].dtype == torch.float32
+            assert us[i].shape == hus[i].shape and us[i].shape[0] >= k and us[i].is_contiguous() and hus[i].is_contiguous()
+            arr[i].u = us[i].data_ptr()
+            arr[i].hu = hus[i].data_ptr()
+            arr[i].stride = us[i].shape[1]
+        self._keep_power = (us, hus)
+        B.triaccel_power_iter(self.handle, arr, k, latch)
+
+    def power_state(self):
+        return B.triaccel_power_state(self.handle, self.n)
+
     def param(self, i: int, code: int) -> torch.Tensor:
         """View of tensor ``i``'s stored parameters as precision ``code`` (take it from layer_state)."""
         return self.buf[i].view(_TORCH_DTYPE[code])[: self.numel[i]]

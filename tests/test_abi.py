@@ -40,16 +40,19 @@ def test_ctypes_layout_matches_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "triaccel.h"\n'
-        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(triaccel_config),"
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(triaccel_config),"
         " sizeof(triaccel_tensor), sizeof(triaccel_step_args), sizeof(triaccel_step_result),"
         " sizeof(triaccel_layer_info), sizeof(triaccel_stage_times), offsetof(triaccel_config, rho_low),"
-        " offsetof(triaccel_tensor, numel), offsetof(triaccel_layer_info, code)); return 0;}\n")
+        " offsetof(triaccel_tensor, numel), offsetof(triaccel_layer_info, code), sizeof(triaccel_power_tensor),"
+        " sizeof(triaccel_power_info), offsetof(triaccel_power_info, deficient),"
+        " offsetof(triaccel_config, lambda_source)); return 0;}\n")
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     want = [C.sizeof(B.Config), C.sizeof(B.Tensor), C.sizeof(B.StepArgs), C.sizeof(B.StepResult),
             C.sizeof(B.LayerInfo), C.sizeof(B.StageTimes), B.Config.rho_low.offset, B.Tensor.numel.offset,
-            B.LayerInfo.code.offset]
+            B.LayerInfo.code.offset, C.sizeof(B.PowerTensor), C.sizeof(B.PowerInfo), B.PowerInfo.deficient.offset,
+            B.Config.lambda_source.offset]
     assert [int(x) for x in out] == want
 
 

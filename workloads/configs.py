@@ -28,7 +28,8 @@ TORCH_DTYPE = {FP16: torch.float16, BF16: torch.bfloat16, FP32: torch.float32}
 
 WORKLOAD_NAMES = ("tiny_mlp", "resnet18", "efficientnet_b0", "large_streaming", "mixed_state")
 
-_KIND = {"grad": 1, "z": 2, "hz": 3, "param": 4, "layer": 5, "hess": 6, "inject": 7, "zero": 8}
+_KIND = {"grad": 1, "z": 2, "hz": 3, "param": 4, "layer": 5, "hess": 6, "inject": 7, "zero": 8, "pstart": 9, "pdiag": 10,
+         "pvec": 11}
 
 
 def _mix(*vals: int) -> int:
@@ -185,6 +186,37 @@ class Workload:
             noise = torch.randn(n, generator=gn, device=device, dtype=torch.float32) * math.sqrt(0.1 * d)
             hz = (z * d + noise) * float(loss_scale)
         return z, hz
+
+    # ---- inputs of the power iteration -----------------------------------------------------
+    POWER_SPIKES = (8.0, 5.0, 3.0, 2.0, 1.25, 0.75)
+
+    def power_start(self, l: int, k: int, device="cpu", stride: Optional[int] = None) -> torch.Tensor:
+        """``k`` standard-normal start vectors for tensor ``l``: fp32, shape (k, stride), stride =
+        numel rounded up to a multiple of 4 unless given; the padding columns are zero."""
+        n = self.numel(l)
+        stride = (n + 3) // 4 * 4 if stride is None else stride
+        g = _gen(device, self.seed, _KIND["pstart"], l)
+        u = torch.zeros(k, stride, device=device, dtype=torch.float32)
+        u[:, :n] = torch.randn(k, n, generator=g, device=device, dtype=torch.float32)
+        return u
+
+    def power_hessian_times(self, l: int, u: torch.Tensor) -> torch.Tensor:
+        """Rows of ``u`` (shape (k, stride), fp32) times a fixed symmetric stand-in for the layer's
+        Hessian, ``H = d_l (diag(a) + sum_r s_r v_r v_r^T)`` with ``a ~ U[0, 0.5]``, six spikes
+        ``s_r`` (POWER_SPIKES) along nearly orthonormal random directions ``v_r``: the kind of
+        product the training framework's double-backward pass would supply.  Padding columns of
+        the result are zero.  Computed with torch in the precision and on the device of ``u``."""
+        n = self.numel(l)
+        dev = u.device
+        d = float(self.layer_consts(l).get("d", 1.0))
+        a = torch.rand(n, generator=_gen(dev, self.seed, _KIND["pdiag"], l), device=dev, dtype=torch.float32) * 0.5
+        v = torch.randn(len(self.POWER_SPIKES), n, generator=_gen(dev, self.seed, _KIND["pvec"], l), device=dev,
+                        dtype=torch.float32) / math.sqrt(n)
+        s = torch.tensor(self.POWER_SPIKES, device=dev, dtype=u.dtype)
+        x = u[:, :n]
+        out = torch.zeros_like(u)
+        out[:, :n] = d * (x * a.to(u.dtype) + ((x @ v.to(u.dtype).T) * s) @ v.to(u.dtype))
+        return out
 
     # ---- block-diagonal quadratic (tiny_mlp) -------------------------------------------
     BLOCK = 32

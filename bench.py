@@ -77,6 +77,11 @@ def main():
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tensors", type=int, default=0, help="use only the first N tensors of the workload (tuning runs)")
+    ap.add_argument("--mode", choices=["step", "power"], default="step",
+                    help="step: the fused optimizer step (default, the headline); power: one power iteration")
+    ap.add_argument("--power-k", type=int, default=5, help="vectors per layer in --mode power (the paper's top-k = 5)")
+    ap.add_argument("--power-stage-times", action="store_true",
+                    help="--mode power: read the kernel times after every call (synchronises each call)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain fp32 copy kernel on 1 GiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -103,6 +108,8 @@ def main():
     if args.all_fp32:
         hyper.update(tau_low=0.0, tau_high=0.0)
     K, W = args.steps, args.warmup
+    if args.mode == "power":
+        return bench_power(args, wl, hyper, dev)
     L, N = wl.n_tensors, wl.total_params
     numel = [wl.numel(l) for l in range(L)]
     grad_size = 4 if wl.grad_dtype == 2 else 2
@@ -226,6 +233,79 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, hyper, sets[0], args.cpu_sample_tensors, scale)
+    opt.close()
+    print(json.dumps(out))
+
+
+def bench_power(args, wl, hyper, dev):
+    """One call = one power iteration (Sec. 3.2) on k vectors for every tensor of the workload."""
+    import torch
+
+    import paper_2508_16905_amd as ta
+
+    K, W, k = args.steps, min(args.warmup, 5), args.power_k
+    L, N = wl.n_tensors, wl.total_params
+    opt = ta.TriAccel(dict(hyper, power_k=k), [wl.init_param(l, device=dev) for l in range(L)], grad_dtype=wl.grad_dtype)
+    us = [wl.power_start(l, k, device=dev) for l in range(L)]
+    # stand-in products with the scale structure of H u (fixed over the timed calls)
+    hus = []
+    for l in range(L):
+        g = torch.Generator(device=dev)
+        g.manual_seed(1000 + l)
+        h = torch.zeros_like(us[l])
+        h[:, : wl.numel(l)] = torch.randn(k, wl.numel(l), generator=g, device=dev) * float(wl.layer_consts(l).get("d", 1.0))
+        hus.append(h)
+    torch.cuda.synchronize()
+    print(f"[bench] power iteration, {wl.name}: {L} tensors, {N} params, k = {k}, "
+          f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated", file=sys.stderr, flush=True)
+    opt.set_profiling(True)
+    for _ in range(W):
+        opt.power_iter(us, hus, k)
+    torch.cuda.synchronize()
+    stage = [0.0, 0.0, 0.0]
+    t0 = time.perf_counter()
+    for _ in range(K):
+        opt.power_iter(us, hus, k)
+        if args.power_stage_times:
+            stage = [a + b for a, b in zip(stage, opt.power_times())]
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    if not args.power_stage_times:
+        stage = [x * K for x in opt.power_times()]   # the last call only
+    stage = [x / K for x in stage]
+    info = opt.power_state()
+    assert all(i.deficient == 0 for i in info)
+    pass_bytes = 8.0 * k * N   # each pass: k vectors read + k vectors read or written, 4 bytes each
+    gram_gbps, apply_gbps = pass_bytes / 1e9 / (stage[0] / 1e3), pass_bytes / 1e9 / (stage[2] / 1e3)
+    dom = ("k_power_gram", stage[0], gram_gbps) if stage[0] >= stage[2] else ("k_power_apply", stage[2], apply_gbps)
+    out = {
+        "metric": "power-iteration throughput (params/s per iteration on k vectors per layer)",
+        "value": N / (ms / 1e3), "unit": "params/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {L} tensors, {N} params, one power iteration on k = {k} fp32 vectors per tensor"},
+        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": dom[2], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dom[2] / HBM_PEAK_GBPS, "alg_bytes_per_launch": pass_bytes, "traffic": None},
+        "step": {"alg_bytes_per_param": 16.0 * k, "alg_GB": 2 * pass_bytes / 1e9,
+                 "GBps": 2 * pass_bytes / 1e9 / (ms / 1e3), "frac_of_peak": 2 * pass_bytes / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS},
+        "stages": {"gram": {"ms": round(stage[0], 4), "GBps": round(gram_gbps, 1)}, "layer": {"ms": round(stage[1], 4)},
+                   "apply": {"ms": round(stage[2], 4), "GBps": round(apply_gbps, 1)}},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        from _runner import to_numpy
+
+        idx = [0]
+        cfg = oracle.OracleConfig.from_hyper(hyper)
+        orc = oracle.OracleTriAccel(cfg, [to_numpy(wl.init_param(l)) for l in idx], [wl.init_dtype(l) for l in idx],
+                                    [wl.grad_dtype] * len(idx))
+        uo = [to_numpy(us[l])[:, : wl.numel(l)].copy() for l in idx]
+        ho = [to_numpy(hus[l])[:, : wl.numel(l)].copy() for l in idx]
+        t0 = time.perf_counter()
+        orc.power_step(uo, ho, k, False)
+        dt = time.perf_counter() - t0
+        n = sum(wl.numel(l) for l in idx)
+        out["cpu_baseline"] = {"value": n / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first tensor ({n} params, k = {k}) of the workload, 1 iteration, {dt:.2f} s wall"}
     opt.close()
     print(json.dumps(out))
 

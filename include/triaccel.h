@@ -229,6 +229,13 @@ int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor *vectors,
 int triaccel_power_state(triaccel_handle h, triaccel_power_info *out, int32_t n);
 
 /*
+ * Wait for the stream and return the durations (ms) of the three kernels of the last
+ * triaccel_power_iter call -- Gram pass, per-layer factorisation, apply pass -- into ms[0..2] (host).
+ * That call must have been made with profiling on (triaccel_set_profiling).
+ */
+int triaccel_power_times_get(triaccel_handle h, float *ms);
+
+/*
  * Utility: convert n fp32 values (device) to `dtype` (device) with the same round-to-nearest-even
  * store the update kernel uses; dtype FP32 copies.  Enqueued on `hip_stream`.  Both pointers
  * 16-byte aligned.

@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     triaccel_layer_state,
     triaccel_power_iter,
     triaccel_power_state,
+    triaccel_power_times_get,
     triaccel_result,
     triaccel_set_profiling,
     triaccel_stage_times_get,

@@ -147,6 +147,7 @@ EXPORTS = {
     "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
     "triaccel_power_iter": (C.c_int, [C.c_void_p, C.POINTER(PowerTensor), C.c_int32, C.c_int32, C.c_int32]),
     "triaccel_power_state": (C.c_int, [C.c_void_p, C.POINTER(PowerInfo), C.c_int32]),
+    "triaccel_power_times_get": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
 }
 
 _lib: Optional[C.CDLL] = None
@@ -258,3 +259,9 @@ def triaccel_power_state(handle, n: int):
     arr = (PowerInfo * n)()
     _check(load_library().triaccel_power_state(handle, arr, n), "triaccel_power_state")
     return arr
+
+
+def triaccel_power_times_get(handle):
+    ms = (C.c_float * 3)()
+    _check(load_library().triaccel_power_times_get(handle, ms), "triaccel_power_times_get")
+    return list(ms)

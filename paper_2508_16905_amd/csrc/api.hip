@@ -70,6 +70,8 @@ struct triaccel_ctx {
   bool power_used[kRing] = {};
   int power_pos = 0;
   bool power_called = false;
+  hipEvent_t power_prof[4] = {};
+  bool power_timed = false;  // the last call recorded its kernel boundaries
   std::vector<PowerLayer> power_host;
 };
 
@@ -132,6 +134,7 @@ void free_ctx(triaccel_ctx* c) {
     if (c->staging_ev[i]) (void)hipEventDestroy(c->staging_ev[i]);
     if (c->power_staging[i]) (void)hipHostFree(c->power_staging[i]);
     if (c->power_ev[i]) (void)hipEventDestroy(c->power_ev[i]);
+    if (c->power_prof[i]) (void)hipEventDestroy(c->power_prof[i]);
   }
   if (c->pinned_res) (void)hipHostFree(c->pinned_res);
   for (auto& set : c->ev)
@@ -457,7 +460,11 @@ int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor* vectors,
                         h->stream));
   TA_HIP(hipEventRecord(h->power_ev[slot], h->stream));
   h->power_used[slot] = true;
-  TA_HIP(launch_power_iter(h->pt, k, latch ? 1 : 0, h->stream));
+  if (h->profiling)
+    for (auto& e : h->power_prof)
+      if (!e) TA_HIP(hipEventCreate(&e));
+  TA_HIP(launch_power_iter(h->pt, k, latch ? 1 : 0, h->stream, h->profiling ? h->power_prof : nullptr));
+  h->power_timed = h->profiling;
   h->power_called = true;
   return TRIACCEL_OK;
 }
@@ -536,6 +543,15 @@ int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_sta
   TA_HIP(hipStreamSynchronize(h->stream));
   for (int i = 0; i < TRIACCEL_N_STAGES; ++i)
     TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[slot][i], h->ev[slot][i + 1]));
+  return TRIACCEL_OK;
+}
+
+int triaccel_power_times_get(triaccel_handle h, float* ms) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!ms) return TRIACCEL_E_NULL_PTR;
+  if (!h->power_called || !h->power_timed) return TRIACCEL_E_NOT_INITIALISED;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  for (int i = 0; i < 3; ++i) TA_HIP(hipEventElapsedTime(&ms[i], h->power_prof[i], h->power_prof[i + 1]));
   return TRIACCEL_OK;
 }
 

@@ -51,7 +51,8 @@ struct PowerTables {
   uint32_t total_segs;
 };
 
-// One iteration on k vectors per tensor: Gram pass, per-layer factorisation, apply pass.
-hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s);
+// One iteration on k vectors per tensor: Gram pass, per-layer factorisation, apply pass.  With
+// `ev` (four events) the boundaries of the three kernels are recorded on the stream.
+hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s, hipEvent_t* ev);
 
 }  // namespace triaccel

@@ -236,31 +236,35 @@ __global__ __launch_bounds__(kThreads) void k_power_apply(const TensorDesc* __re
 }
 
 template <int K>
-hipError_t launch_k(const PowerTables& t, int latch, hipStream_t s) {
+hipError_t launch_k(const PowerTables& t, int latch, hipStream_t s, hipEvent_t* ev) {
+  hipError_t e;
+  if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
   hipLaunchKernelGGL(k_power_gram<K>, dim3(t.total_segs), dim3(kThreads), 0, s, t.tensors, t.descs, t.segs, t.partials);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
   hipLaunchKernelGGL(k_power_layer<K>, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.seg_first, t.partials,
                      t.state, t.layers, latch);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
   hipLaunchKernelGGL(k_power_apply<K>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.descs, t.chunks,
                      t.state);
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
+  return hipSuccess;
 }
 
 }  // namespace
 
-hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s) {
+hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s, hipEvent_t* ev) {
   switch (k) {
-    case 1: return launch_k<1>(t, latch, s);
-    case 2: return launch_k<2>(t, latch, s);
-    case 3: return launch_k<3>(t, latch, s);
-    case 4: return launch_k<4>(t, latch, s);
-    case 5: return launch_k<5>(t, latch, s);
-    case 6: return launch_k<6>(t, latch, s);
-    case 7: return launch_k<7>(t, latch, s);
-    case 8: return launch_k<8>(t, latch, s);
+    case 1: return launch_k<1>(t, latch, s, ev);
+    case 2: return launch_k<2>(t, latch, s, ev);
+    case 3: return launch_k<3>(t, latch, s, ev);
+    case 4: return launch_k<4>(t, latch, s, ev);
+    case 5: return launch_k<5>(t, latch, s, ev);
+    case 6: return launch_k<6>(t, latch, s, ev);
+    case 7: return launch_k<7>(t, latch, s, ev);
+    case 8: return launch_k<8>(t, latch, s, ev);
     default: return hipErrorInvalidValue;
   }
 }

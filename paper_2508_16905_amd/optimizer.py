@@ -93,6 +93,10 @@ class TriAccel:
     def power_state(self):
         return B.triaccel_power_state(self.handle, self.n)
 
+    def power_times(self):
+        """[Gram pass, per-layer kernel, apply pass] in ms of the last power_iter call (profiling on)."""
+        return B.triaccel_power_times_get(self.handle)
+
     def param(self, i: int, code: int) -> torch.Tensor:
         """View of tensor ``i``'s stored parameters as precision ``code`` (take it from layer_state)."""
         return self.buf[i].view(_TORCH_DTYPE[code])[: self.numel[i]]

@@ -107,3 +107,42 @@ def test_mixed_state_full_size_sampled_tensors_with_overflow():
     assert skipped[6] == 1 and skipped[13] == 1
     assert inj14 not in sample  # the second injection hits a tensor the oracle does not hold
     assert set(codes) == {0, 1, 2}
+
+
+def test_power_iteration_full_size_sampled_tensors():
+    """64 x 4096 x 4096 with k = 5 vectors per tensor (43 GB of vectors): the oracle follows two
+    whole tensors; every tensor's new vectors are checked for orthonormality with library
+    reductions on the GPU, and its Rayleigh quotients against library dot products."""
+    dev = torch.device("cuda:0")
+    wl = get_workload("large_streaming")
+    L, k = wl.n_tensors, 5
+    opt = ta.TriAccel(dict(wl.hyper, power_k=k), [wl.init_param(l, device=dev) for l in range(L)],
+                      grad_dtype=wl.grad_dtype)
+    sample = [3, 41]
+    us = [wl.power_start(l, k, device=dev) for l in range(L)]
+    hus = [wl.power_hessian_times(l, us[l]) for l in range(L)]
+    u_in = {l: to_numpy(us[l]).copy() for l in sample}
+    # quotients from library reductions, before the call overwrites u
+    want_ray = [((us[l].double() * hus[l].double()).sum(1) / (us[l].double() ** 2).sum(1)).cpu().numpy() for l in range(L)]
+    opt.power_iter(us, hus, k, latch=True)
+    info = opt.power_state()
+    for l in range(L):
+        assert info[l].deficient == 0
+        assert np.allclose(np.array(info[l].rayleigh[:k]), want_ray[l], rtol=1e-6, atol=0), l
+        g = (us[l].double() @ us[l].double().T).cpu().numpy()
+        assert np.max(np.abs(g - np.eye(k))) < 1e-6, (l, g)
+    cfg = oracle.OracleConfig.from_hyper(wl.hyper)
+    orc = oracle.OracleTriAccel(cfg, [np.zeros(wl.numel(l), dtype=np.float32) for l in sample], [FP32] * len(sample),
+                                [wl.grad_dtype] * len(sample))
+    uo = [u_in[l] for l in sample]
+    orc.power_step(uo, [to_numpy(hus[l]) for l in sample], k, True)
+    for pos, l in enumerate(sample):
+        t = orc.tensors[pos]
+        assert np.all(np.abs(np.array(info[l].rayleigh[:k]) - t.rayleigh) <= 2 * 2.0 ** -23 * np.abs(t.rayleigh))
+        assert np.all(np.abs(np.array(info[l].hnorm[:k]) - t.hnorm) <= 2 * 2.0 ** -23 * np.abs(t.hnorm))
+        want = uo[pos].reshape(k, -1)
+        got = to_numpy(us[l])
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        assert np.all(err <= 2 * 2.0 ** -23 * np.abs(want) + 1e-11 * np.max(np.abs(want))), (l, float(err.max()))
+        assert abs(info[l].lambda_latched - t.lam_power) <= 2 * 2.0 ** -23 * abs(t.lam_power)
+    opt.close()

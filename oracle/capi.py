@@ -50,6 +50,7 @@ def lib() -> C.CDLL:
         "oracle_grad_stats": (None, [vp, C.c_int, i64, f32, P(f64), P(f64)]),
         "oracle_var_ema": (f32, [f32, f64, f32, C.c_int]),
         "oracle_curv_ema": (None, [vp, vp, vp, i64, f32, f32, C.c_int, P(u32)]),
+        "oracle_fisher_ema": (None, [vp, C.c_int, vp, i64, f32, f32, C.c_int, P(u32)]),
         "oracle_topk_count": (i64, [i64, u32]),
         "oracle_threshold_mask": (None, [vp, i64, u32, vp, P(f32), P(u32), P(f32)]),
         "oracle_precision_code": (C.c_int, [f32, f32, f32, f32, f32]),

@@ -40,6 +40,7 @@ class OracleConfig:
     delta_down: int = 16
     b_min: int = 16
     b_max: int = 4096
+    curvature_source: int = 0    # sample behind the diagonal EMA: 0 = Hutchinson pair z * Hz, 1 = squared gradient
     lambda_source: int = 0       # lambda_l of Sec. 3.2: 0 = largest kept |h_i| of the diagonal EMA,
                                  # 1 = largest |Rayleigh quotient| of the latched power iteration
 
@@ -120,7 +121,7 @@ class OracleTriAccel:
             self._executor = ThreadPoolExecutor(self.workers)
         return self._executor
 
-    def _tensor_step(self, t, g, z, hz, lr, inv_scale, control_step, first):
+    def _tensor_step(self, t, g, z, hz, lr, inv_scale, control_step, first, update_curvature):
         L, cfg, f32 = lib(), self.cfg, np.float32
         # (1) collect per-layer gradient variance ...
         mean, var = C.c_double(), C.c_double()
@@ -129,10 +130,15 @@ class OracleTriAccel:
         t.v = f32(L.oracle_var_ema(t.v, var.value, f32(cfg.beta_var), int(first)))
         # ... and curvature statistics
         t.curv_nonfinite = 0
-        if z is not None:
+        fisher = cfg.curvature_source == 1
+        if (update_curvature if fisher else z is not None):
             flag = C.c_uint32(0)
-            L.oracle_curv_ema(z.ctypes.data, hz.ctypes.data, t.curv.ctypes.data, t.numel, inv_scale,
-                              f32(cfg.beta_curv), int(t.probes_seen == 0), C.byref(flag))
+            if fisher:
+                L.oracle_fisher_ema(g.ctypes.data, t.grad_dtype, t.curv.ctypes.data, t.numel, inv_scale,
+                                    f32(cfg.beta_curv), int(t.probes_seen == 0), C.byref(flag))
+            else:
+                L.oracle_curv_ema(z.ctypes.data, hz.ctypes.data, t.curv.ctypes.data, t.numel, inv_scale,
+                                  f32(cfg.beta_curv), int(t.probes_seen == 0), C.byref(flag))
             t.curv_nonfinite = int(flag.value)
             t.probes_seen += 1
             theta, nnz, lam = C.c_float(), C.c_uint32(), C.c_float()
@@ -174,9 +180,10 @@ class OracleTriAccel:
 
     def step(self, grads: Sequence[np.ndarray], zs: Sequence[Optional[np.ndarray]],
              hzs: Sequence[Optional[np.ndarray]], lr: float, loss_scale: float, batch_size: int,
-             mem_used: int, mem_total: int, overflow_elsewhere: bool = False) -> dict:
+             mem_used: int, mem_total: int, overflow_elsewhere: bool = False, update_curvature: bool = True) -> dict:
         """``overflow_elsewhere``: a tensor that this oracle does not hold (when it tracks a subset
-        of a larger parameter set) had a non-finite gradient, so the step is skipped for all."""
+        of a larger parameter set) had a non-finite gradient, so the step is skipped for all.
+        ``update_curvature``: with ``curvature_source == 1``, whether this step updates the EMA."""
         L, cfg = lib(), self.cfg
         f32 = np.float32
         inv_scale = f32(1.0) / f32(loss_scale)
@@ -193,7 +200,8 @@ class OracleTriAccel:
             first = self.applied_steps == 1
 
             def one(args):
-                self._tensor_step(*args, lr=lr, inv_scale=inv_scale, control_step=control_step, first=first)
+                self._tensor_step(*args, lr=lr, inv_scale=inv_scale, control_step=control_step, first=first,
+                                  update_curvature=update_curvature)
 
             work = list(zip(self.tensors, grads, zs, hzs))
             if self.workers > 1:

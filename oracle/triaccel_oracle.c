@@ -169,6 +169,24 @@ void oracle_curv_ema(const float *z, const float *hz, float *h, int64_t n,
     }
 }
 
+/* Empirical-Fisher variant of the same signal ("Hessian or Fisher", Sec. 1 and
+ * 3.2): the sample is the squared unscaled gradient, u_i = (g_i / S)^2, no
+ * probe.  Same EMA, same non-finite rule (the square can overflow).
+ * fp32: x = fp32(g_i) * inv_scale, u = x * x, h = fma(beta_h, h, fp32((1 - beta_h) * u)). */
+void oracle_fisher_ema(const void *g, int g_dtype, float *h, int64_t n, float inv_scale,
+                       float beta_h, int first, uint32_t *nonfinite)
+{
+    const float omb = 1.0f - beta_h;
+    for (int64_t i = 0; i < n; ++i) {
+        float x = widen(g, g_dtype, i) * inv_scale;
+        float u = x * x;
+        if (!isfinite(u)) { *nonfinite = 1; continue; }
+        if (first) { h[i] = u; continue; }
+        float p = omb * u;
+        h[i] = fmaf(beta_h, h[i], p);
+    }
+}
+
 /* ------------------------------------------------------------------------ */
 /* Sparsification of the curvature ("top-k Hessian or Fisher entries", Sec. 1
  * and 3.2).  Plain definition by sorting:

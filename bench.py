@@ -48,7 +48,7 @@ def measured_traffic(workload, all_fp32, n_tensors_limit):
     return MEASURED_TRAFFIC["fetch_bytes"] + MEASURED_TRAFFIC["write_bytes"]
 
 
-def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum):
+def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False):
     """Bytes each stage must move for one step, from the definitions of the stages:
     statistics read g; the EMA reads z, Hz, h and writes h; the mask pass re-reads h and writes one
     bit per element; the update reads g, the stored parameter and m, and writes the parameter and m."""
@@ -57,7 +57,8 @@ def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, m
     for n, pc, c, extra in zip(numel, prev_codes, codes, sel_passes):
         b["grad_stats"] += n * grad_size
         if probed:
-            b["curv_ema"] += n * 16
+            # Hutchinson source: z, Hz, h read, h written; Fisher source: g, h read, h written
+            b["curv_ema"] += n * ((grad_size + 8) if fisher else 16)
             # the exact threshold needs |h| once more after the pass that creates it; that re-read is
             # part of the method's traffic whether or not the prediction lets the kernels skip it
             b["mask_fallback" if extra else "mask_in_ema"] += n * 4 + n / 8.0
@@ -73,6 +74,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="large_streaming")
     ap.add_argument("--all-fp32", action="store_true", help="thresholds that keep every layer in FP32")
+    ap.add_argument("--fisher", action="store_true",
+                    help="curvature sample = squared gradient (no probe pairs) instead of the Hutchinson pair")
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -107,6 +110,8 @@ def main():
     hyper = dict(wl.hyper)
     if args.all_fp32:
         hyper.update(tau_low=0.0, tau_high=0.0)
+    if args.fisher:
+        hyper.update(curvature_source=1)
     K, W = args.steps, args.warmup
     if args.mode == "power":
         return bench_power(args, wl, hyper, dev)
@@ -125,6 +130,9 @@ def main():
     gen_steps = [t for t in range(1, 4 * R + 2) if not (wl.inject_every and t % wl.inject_every == 0)][:R]
     for t in gen_steps:
         grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
+        if args.fisher:
+            sets.append((grads, None, None))
+            continue
         pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
         sets.append((grads, [p[0] for p in pr], [p[1] for p in pr]))
     torch.cuda.synchronize()
@@ -175,7 +183,8 @@ def main():
     # unless a layer switched; the count of switches is reported)
     switched = sum(1 for a, b in zip(codes_before, codes) if a != b)
     sel_passes = [s.sel_passes for s in state]
-    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, True, hyper["momentum"] != 0.0)
+    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, True, hyper["momentum"] != 0.0,
+                            fisher=args.fisher)
     total_bytes = sum(alg.values())
     # bytes each kernel stage actually has to move in the last timed step
     moved = {"grad_stats": alg["grad_stats"], "curv_ema": alg["curv_ema"] + alg["mask_in_ema"] / 33.0,
@@ -207,6 +216,7 @@ def main():
             "workload": f"{wl.name}: {L} tensors, {N} params, fp{8 * grad_size} gradients, probe every step, "
                         f"momentum {hyper['momentum']}, sparsity {hyper['sparsity_ppm'] / 1e4:.0f}%",
             "all_fp32": bool(args.all_fp32),
+            "curvature_source": "empirical Fisher (squared gradient)" if args.fisher else "Hutchinson pair (z, Hz)",
             "codes": {"fp16": codes.count(0), "bf16": codes.count(1), "fp32": codes.count(2)},
             "layers_switched_in_timed_region": switched,
             "tensors_needing_extra_passes_over_h_last_step": sum(1 for x in sel_passes if x),
@@ -325,8 +335,8 @@ def cpu_baseline(wl, hyper, first_set, n_sample, scale):
     orc = oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx),
                                 workers=cores)
     g = [to_numpy(first_set[0][l]) for l in idx]
-    z = [to_numpy(first_set[1][l]) for l in idx]
-    hz = [to_numpy(first_set[2][l]) for l in idx]
+    z = [None if first_set[1] is None else to_numpy(first_set[1][l]) for l in idx]
+    hz = [None if first_set[2] is None else to_numpy(first_set[2][l]) for l in idx]
     t0 = time.perf_counter()
     orc.step(g, z, hz, float(hyper["lr"]), scale, int(hyper["batch_size"]), 8, 10)
     dt = time.perf_counter() - t0

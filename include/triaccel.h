@@ -78,6 +78,9 @@ typedef struct {
   int32_t lambda_source;   /* lambda_l of the step-size and promotion rules (Sec. 3.2):
                               0 = largest kept |h_i| of the diagonal curvature EMA,
                               1 = max_j |Rayleigh quotient| latched by triaccel_power_iter            */
+  int32_t curvature_source; /* sample behind the diagonal curvature EMA ("Hessian or Fisher", Sec. 1 / 3.2):
+                              0 = Hutchinson pair, u_i = z_i (Hz)_i / S (the caller supplies z and hz),
+                              1 = empirical Fisher, u_i = (g_i / S)^2 (no probe; z and hz must be NULL)  */
 } triaccel_config;
 
 /* One parameter tensor.  Contiguous, flat; numel elements. */
@@ -104,6 +107,11 @@ typedef struct {
   int32_t batch_size;       /* B(t), input of the batch rule                                        */
   uint64_t mem_used_bytes;  /* MemUsage(t); with mem_total_bytes == 0 the library asks the HIP      */
   uint64_t mem_total_bytes; /* MemMax       runtime (hipMemGetInfo) for both                        */
+  int32_t update_curvature; /* only read with curvature_source == 1: non-zero = this step refreshes the
+                               curvature EMA, threshold and mask from its gradient (the "every T
+                               iterations" of Sec. 3.2 is the caller's schedule); with curvature_source
+                               == 0 the presence of z decides, per tensor                              */
+  int32_t reserved_;        /* set to 0 */
 } triaccel_step_args;
 
 typedef struct {

@@ -44,9 +44,10 @@ class Config(C.Structure):
         ("b_max", C.c_int32),
         ("power_k", C.c_int32),
         ("lambda_source", C.c_int32),
+        ("curvature_source", C.c_int32),
     ]
     # fields a hyper-parameter dict may leave out
-    _OPTIONAL = {"power_k": 0, "lambda_source": 0}
+    _OPTIONAL = {"power_k": 0, "lambda_source": 0, "curvature_source": 0}
 
     @classmethod
     def from_hyper(cls, hyper: dict) -> "Config":
@@ -80,6 +81,8 @@ class StepArgs(C.Structure):
         ("batch_size", C.c_int32),
         ("mem_used_bytes", C.c_uint64),
         ("mem_total_bytes", C.c_uint64),
+        ("update_curvature", C.c_int32),
+        ("reserved_", C.c_int32),
     ]
 
 
@@ -199,11 +202,12 @@ def triaccel_init(config: Config, tensors: Sequence[Tensor], stream: int = 0) ->
 
 
 def triaccel_step(handle, tensors, lr: float, loss_scale: float, batch_size: int = 0, mem_used_bytes: int = 0,
-                  mem_total_bytes: int = 0) -> None:
+                  mem_total_bytes: int = 0, update_curvature: bool = True) -> None:
     """``tensors`` is a ctypes array ``(Tensor * n)`` or a sequence of ``Tensor``."""
     lib = load_library()
     arr = tensors if isinstance(tensors, C.Array) else (Tensor * len(tensors))(*tensors)
-    args = StepArgs(C.sizeof(StepArgs), lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes)
+    args = StepArgs(C.sizeof(StepArgs), lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes,
+                    int(update_curvature), 0)
     _check(lib.triaccel_step(handle, arr, len(arr), C.byref(args)), "triaccel_step")
 
 

@@ -110,6 +110,7 @@ int validate_config(const triaccel_config* cfg) {
   if (cfg->power_k < 0 || cfg->power_k > kMaxPowerK) return TRIACCEL_E_INVALID_ARG;
   if (cfg->lambda_source != 0 && cfg->lambda_source != 1) return TRIACCEL_E_INVALID_ARG;
   if (cfg->lambda_source == 1 && cfg->power_k == 0) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->curvature_source != 0 && cfg->curvature_source != 1) return TRIACCEL_E_INVALID_ARG;
   return TRIACCEL_OK;
 }
 
@@ -311,14 +312,17 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   if (!(args->loss_scale > 0.0f) || !std::isfinite(args->loss_scale) || !std::isfinite(args->lr))
     return TRIACCEL_E_INVALID_ARG;
   const bool need_mom = h->cfg.momentum != 0.0f;
+  const bool fisher = h->cfg.curvature_source == 1;
   bool any_probe = false;
   for (int32_t i = 0; i < n; ++i) {
     const triaccel_tensor& t = tensors[i];
     if (t.numel != h->numel[i] || t.grad_dtype != h->grad_dtype[i]) return TRIACCEL_E_SHAPE_MISMATCH;
     const int rc = validate_tensor(t, need_mom);
     if (rc) return rc;
+    if (fisher && t.z != nullptr) return TRIACCEL_E_INVALID_ARG;  // no probe pairs in this mode
     any_probe = any_probe || t.z != nullptr;
   }
+  if (fisher) any_probe = args->update_curvature != 0;
   // stage (4) of the control loop: batch size from memory usage, on the host
   uint64_t used = args->mem_used_bytes, total = args->mem_total_bytes;
   if (total == 0) {
@@ -339,7 +343,7 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
     d.curv = t.curv;
     d.mom = need_mom ? t.mom : nullptr;
     d.mask = t.mask;
-    d.has_probe = t.z != nullptr;
+    d.has_probe = fisher ? (any_probe ? 1 : 0) : (t.z != nullptr);
   }
   const size_t table_bytes = (size_t)n * sizeof(TensorDesc);
   if (!h->desc_valid || std::memcmp(h->desc.data(), h->desc_sent.data(), table_bytes) != 0) {
@@ -374,7 +378,7 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   if (prof) TA_HIP(hipEventRecord(ev[0], s));
   TA_HIP(launch_grad_stats(T, sc, s));
   if (prof) TA_HIP(hipEventRecord(ev[1], s));
-  if (any_probe) TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, s));
+  if (any_probe) TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, fisher ? 1 : 0, s));
   if (prof) TA_HIP(hipEventRecord(ev[2], s));
   TA_HIP(launch_layer(T, sc, h->hp, s));
   if (prof) TA_HIP(hipEventRecord(ev[3], s));

@@ -26,7 +26,8 @@ struct DeviceTables {
 };
 
 hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
-hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s);
+hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, int fisher,
+                           hipStream_t s);
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);

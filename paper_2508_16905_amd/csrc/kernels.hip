@@ -296,7 +296,9 @@ __device__ __forceinline__ void for_each_candidate(const TensorDesc& td, const C
 // record per chunk (keys above the band, zero keys, largest key, non-finite flag); no atomics
 // except the candidate appends.
 // ---------------------------------------------------------------------------------------------
-template <bool FULL>
+// SRC selects the sample: -1 = Hutchinson pair z * Hz / S; a precision code = squared unscaled
+// gradient (g / S)^2 read from the gradient buffer of that precision (empirical Fisher).
+template <bool FULL, int SRC>
 __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, float inv_scale, float beta_h,
                                           float omb_h, bool first, bool band, bool list_all, uint32_t band_lo,
                                           uint32_t band_hi, uint32_t chunk_index, uint32_t tensor, Candidate* cands,
@@ -308,15 +310,23 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = base + r * kRowElems + tid * kVec;
-    if (FULL) {
-      load4<kFP32>(td.z, idx, z[r]);
-      load4<kFP32>(td.hz, idx, hz[r]);
-      load4<kFP32>(td.curv, idx, h[r]);
+    if constexpr (SRC < 0) {
+      if (FULL) {
+        load4<kFP32>(td.z, idx, z[r]);
+        load4<kFP32>(td.hz, idx, hz[r]);
+      } else {
+        load4_guard<kFP32>(td.z, idx, td.numel, 0.0f, z[r]);
+        load4_guard<kFP32>(td.hz, idx, td.numel, 0.0f, hz[r]);
+      }
     } else {
-      load4_guard<kFP32>(td.z, idx, td.numel, 0.0f, z[r]);
-      load4_guard<kFP32>(td.hz, idx, td.numel, 0.0f, hz[r]);
-      load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
+      // x = g / S in both factors: u = x * x
+      if (FULL) load4<SRC>(td.grad, idx, z[r]);
+      else load4_guard<SRC>(td.grad, idx, td.numel, 0.0f, z[r]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) hz[r][i] = z[r][i] = z[r][i] * inv_scale;
     }
+    if (FULL) load4<kFP32>(td.curv, idx, h[r]);
+    else load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
   }
   uint32_t word[kRows];
   uint32_t cflags = 0;
@@ -327,7 +337,7 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float u = z[r][i] * hz[r][i];
-      u = u * inv_scale;
+      if constexpr (SRC < 0) u = u * inv_scale;
       float hn = h[r][i];
       const bool valid = FULL || idx + i < td.numel;
       if ((f2u(u) & 0x7f800000u) == 0x7f800000u) {
@@ -370,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restr
                                                        const ChunkRef* __restrict__ chunks, const LayerDev* layers,
                                                        const GlobalDev* glob, EmaPartial* __restrict__ ema_partials,
                                                        Candidate* cands, uint32_t* counters, StepScalars sc,
-                                                       float beta_h, float omb_h) {
+                                                       float beta_h, float omb_h, int fisher) {
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
   const TensorDesc td = tds[cr.tensor];
@@ -382,12 +392,30 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restr
   const uint32_t band_lo = ls.band_lo, band_hi = ls.band_hi;
   const int64_t base = (int64_t)cr.index * kChunk;
   uint32_t above_zeros = 0, maxkey = 0, nonfin = 0;
-  if (base + kChunk <= td.numel)
-    ema_chunk<true>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index,
-                    cr.tensor, cands, counters, above_zeros, maxkey, nonfin);
-  else
-    ema_chunk<false>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index,
-                     cr.tensor, cands, counters, above_zeros, maxkey, nonfin);
+#define TA_EMA(FULL_, SRC_)                                                                                   \
+  ema_chunk<FULL_, SRC_>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index, \
+                         cr.tensor, cands, counters, above_zeros, maxkey, nonfin)
+  const bool full = base + kChunk <= td.numel;
+  if (!fisher) {
+    if (full) TA_EMA(true, -1);
+    else TA_EMA(false, -1);
+  } else {
+    switch (td.grad_dtype) {
+      case kFP32:
+        if (full) TA_EMA(true, kFP32);
+        else TA_EMA(false, kFP32);
+        break;
+      case kBF16:
+        if (full) TA_EMA(true, kBF16);
+        else TA_EMA(false, kBF16);
+        break;
+      default:
+        if (full) TA_EMA(true, kFP16);
+        else TA_EMA(false, kFP16);
+        break;
+    }
+  }
+#undef TA_EMA
   // per-chunk record: fixed-order reduction over lanes and wavefronts, one plain store
   above_zeros = wave_sum(above_zeros);  // at most 4096 in either half: no carry between the halves
   maxkey = wave_max(maxkey);
@@ -1288,9 +1316,10 @@ hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipSt
   return hipSuccess;
 }
 
-hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, hipStream_t s) {
+hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, int fisher,
+                           hipStream_t s) {
   hipLaunchKernelGGL(k_curv_ema, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                     t.ema_partials, t.cands, t.cand_counters, sc, beta_h, omb_h);
+                     t.ema_partials, t.cands, t.cand_counters, sc, beta_h, omb_h, fisher);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

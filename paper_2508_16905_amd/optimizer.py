@@ -59,7 +59,8 @@ class TriAccel:
 
     def step(self, grads: Sequence[torch.Tensor], zs: Optional[Sequence[Optional[torch.Tensor]]] = None,
              hzs: Optional[Sequence[Optional[torch.Tensor]]] = None, lr: float = 0.1, loss_scale: float = 1.0,
-             batch_size: int = 0, mem_used_bytes: int = 0, mem_total_bytes: int = 0) -> None:
+             batch_size: int = 0, mem_used_bytes: int = 0, mem_total_bytes: int = 0,
+             update_curvature: bool = True) -> None:
         """Enqueue one step (asynchronous).  The caller keeps ``grads``/``zs``/``hzs`` alive until
         the stream has passed the step; a reference is also held here until the next call."""
         for i in range(self.n):
@@ -69,7 +70,8 @@ class TriAccel:
             t.z = None if z is None else z.data_ptr()
             t.hz = None if z is None else hzs[i].data_ptr()
         self._keep = (grads, zs, hzs)
-        B.triaccel_step(self.handle, self._tensors, lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes)
+        B.triaccel_step(self.handle, self._tensors, lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes,
+                        update_curvature)
 
     def result(self) -> B.StepResult:
         return B.triaccel_result(self.handle)

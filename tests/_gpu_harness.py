@@ -61,7 +61,7 @@ class Pair:
             zs = hzs = [None] * wl.n_tensors
         return grads, zs, hzs
 
-    def step(self, grads, zs, hzs, lr=None, mem=(800, 1000), check=True, label=""):
+    def step(self, grads, zs, hzs, lr=None, mem=(800, 1000), check=True, label="", update_curvature=True):
         """One step on both sides from CPU torch tensors; returns the oracle's result dict."""
         wl = self.wl
         self.t += 1
@@ -71,10 +71,10 @@ class Pair:
         z_d = [None if z is None else z.to(dev) for z in zs]
         hz_d = [None if h is None else h.to(dev) for h in hzs]
         self.gpu.step(g_d, z_d, hz_d, lr=lr, loss_scale=self.scale, batch_size=self.batch,
-                      mem_used_bytes=mem[0], mem_total_bytes=mem[1])
+                      mem_used_bytes=mem[0], mem_total_bytes=mem[1], update_curvature=update_curvature)
         res_o = self.orc.step([to_numpy(g) for g in grads], [None if z is None else to_numpy(z) for z in zs],
                               [None if h is None else to_numpy(h) for h in hzs], lr, self.scale, self.batch,
-                              mem[0], mem[1])
+                              mem[0], mem[1], update_curvature=update_curvature)
         res_g = self.gpu.result()
         where = f"{wl.name} step {self.t} {label}"
         assert res_g.skipped == res_o["skipped"], where

@@ -215,3 +215,25 @@ def test_harness_detects_a_mistake_planted_in_the_oracle():
         undo()
     p.compare("restored")
     p.close()
+
+
+@pytest.mark.parametrize("gd", [FP32, FP16, BF16])
+def test_empirical_fisher_curvature_source(gd):
+    # the curvature sample is the squared unscaled gradient; no probe pairs; every third step leaves
+    # the curvature state alone
+    sizes = [1, 33, 4096, 4097, 8193, 70001, 300007]
+    wl = custom(sizes, grad_dtype=gd, loss_scale=1.0 if gd == FP32 else 1024.0, curvature_source=1, steps=12,
+                tau_curv=1e-5)
+    p = Pair(wl)
+    none = [None] * len(sizes)
+    for t in range(1, 13):
+        g, _, _ = p.inputs(t, probe=False)
+        p.step(g, none, none, update_curvature=(t % 3 != 0))
+    assert all(o.probes_seen == 8 for o in p.orc.tensors) and any(o.nnz > 0 for o in p.orc.tensors)
+    # probe pairs are refused in this mode, and change nothing
+    import paper_2508_16905_amd as ta
+    g, z, hz = p.inputs(13, probe=True)
+    with pytest.raises(ta.TriAccelError):
+        p.gpu.step([x.to(p.device) for x in g], [x.to(p.device) for x in z], [x.to(p.device) for x in hz])
+    p.compare("after the refused call")
+    p.close()

@@ -200,6 +200,21 @@ int triaccel_set_profiling(triaccel_handle h, int32_t on);
 int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_stage_times *out);
 
 /*
+ * Checkpointing (for callers that cannot re-run a job from step 0).  The tensors are the caller's; what the
+ * library holds is small: the per-layer records (variance EMA, codes, latched curvature, threshold
+ * predictor, power-iteration lambda), the loss-scale counter and the step count.
+ * triaccel_state_size returns the number of bytes of the blob (negative error code on failure);
+ * triaccel_get_state waits for the stream and writes the blob to `buf` (host, `size` bytes as returned);
+ * triaccel_set_state replaces the state of a handle created with the same tensor list (same n, numel and
+ * gradient dtypes) and the same hyper-parameters; a blob that does not match is refused and nothing changes.
+ * After set_state, with the caller's tensors restored to their saved contents, the following steps are
+ * bit-identical to those of the run that saved the state.
+ */
+int64_t triaccel_state_size(triaccel_handle h);
+int triaccel_get_state(triaccel_handle h, void *buf, int64_t size);
+int triaccel_set_state(triaccel_handle h, const void *buf, int64_t size);
+
+/*
  * Power iteration for the top-k eigenvalues of each layer's Hessian (Sec. 3.2, third equation:
  * u <- H u / ||H u||, lambda ~ u^T H u / u^T u).  The caller owns the Hessian-vector products; one
  * call performs one iteration on k vectors per layer.  On entry u holds the current vectors u_j and

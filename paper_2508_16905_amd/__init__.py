@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     triaccel_batch_next,
     triaccel_cast_f32,
     triaccel_destroy,
+    triaccel_get_state,
+    triaccel_set_state,
     triaccel_init,
     triaccel_layer_state,
     triaccel_power_iter,

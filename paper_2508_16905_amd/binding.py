@@ -148,6 +148,9 @@ EXPORTS = {
     "triaccel_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "triaccel_stage_times_get": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(StageTimes)]),
     "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
+    "triaccel_state_size": (C.c_int64, [C.c_void_p]),
+    "triaccel_get_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64]),
+    "triaccel_set_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64]),
     "triaccel_power_iter": (C.c_int, [C.c_void_p, C.POINTER(PowerTensor), C.c_int32, C.c_int32, C.c_int32]),
     "triaccel_power_state": (C.c_int, [C.c_void_p, C.POINTER(PowerInfo), C.c_int32]),
     "triaccel_power_times_get": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
@@ -269,3 +272,17 @@ def triaccel_power_times_get(handle):
     ms = (C.c_float * 3)()
     _check(load_library().triaccel_power_times_get(handle, ms), "triaccel_power_times_get")
     return list(ms)
+
+
+def triaccel_get_state(handle) -> bytes:
+    lib = load_library()
+    size = lib.triaccel_state_size(handle)
+    if size < 0:
+        raise TriAccelError(int(size), "triaccel_state_size")
+    buf = C.create_string_buffer(size)
+    _check(lib.triaccel_get_state(handle, buf, size), "triaccel_get_state")
+    return buf.raw
+
+
+def triaccel_set_state(handle, blob: bytes) -> None:
+    _check(load_library().triaccel_set_state(handle, blob, len(blob)), "triaccel_set_state")

@@ -57,6 +57,7 @@ struct triaccel_ctx {
   int ring_pos = 0;
   GlobalDev* pinned_res = nullptr;
   uint64_t step_index = 0;
+  bool result_valid = false;  // a step has been enqueued since init / set_state
   int32_t next_batch = 0;
   bool profiling = false;
   hipEvent_t ev[TRIACCEL_PROFILE_RING][TRIACCEL_N_STAGES + 1] = {};
@@ -400,6 +401,7 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
 
   h->next_batch = next_batch;
+  h->result_valid = true;
   return TRIACCEL_OK;
 }
 
@@ -407,7 +409,7 @@ int triaccel_result(triaccel_handle h, triaccel_step_result* out) {
   if (!h) return TRIACCEL_E_NOT_INITIALISED;
   if (!out) return TRIACCEL_E_NULL_PTR;
   if (out->struct_size != sizeof(triaccel_step_result)) return TRIACCEL_E_INVALID_ARG;
-  if (h->step_index == 0) return TRIACCEL_E_NOT_INITIALISED;
+  if (h->step_index == 0 || !h->result_valid) return TRIACCEL_E_NOT_INITIALISED;
   TA_HIP(hipStreamSynchronize(h->stream));
   out->skipped = h->pinned_res->res_skipped;
   out->step_index = h->step_index;
@@ -442,6 +444,82 @@ int triaccel_layer_state(triaccel_handle h, triaccel_layer_info* out, int32_t n)
     o.sel_listed = ls.sel_listed;
     o.sel_outcome = ls.sel_outcome;
   }
+  return TRIACCEL_OK;
+}
+
+namespace {
+struct StateHeader {
+  uint64_t magic;       // "TRIACCL1"
+  uint32_t layer_size;  // sizeof(LayerDev): guards against a blob from another build
+  uint32_t n;
+  uint64_t step_index;
+  int32_t next_batch;
+  int32_t good_steps;
+  uint64_t shape_hash;  // over numel and gradient dtypes
+  uint64_t config_hash; // over the hyper-parameters
+};
+constexpr uint64_t kStateMagic = 0x314c434341495254ull;
+
+uint64_t fnv1a(const void* data, size_t bytes, uint64_t h = 1469598103934665603ull) {
+  const unsigned char* p = static_cast<const unsigned char*>(data);
+  for (size_t i = 0; i < bytes; ++i) h = (h ^ p[i]) * 1099511628211ull;
+  return h;
+}
+uint64_t shape_hash(const triaccel_ctx* c) {
+  uint64_t h = fnv1a(c->numel.data(), c->numel.size() * sizeof(int64_t));
+  return fnv1a(c->grad_dtype.data(), c->grad_dtype.size() * sizeof(int32_t), h);
+}
+}  // namespace
+
+int64_t triaccel_state_size(triaccel_handle h) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  return (int64_t)(sizeof(StateHeader) + (size_t)h->n * sizeof(LayerDev));
+}
+
+int triaccel_get_state(triaccel_handle h, void* buf, int64_t size) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!buf) return TRIACCEL_E_NULL_PTR;
+  if (size != triaccel_state_size(h)) return TRIACCEL_E_INVALID_ARG;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  GlobalDev g;
+  TA_HIP(hipMemcpy(&g, h->t.glob, sizeof(g), hipMemcpyDeviceToHost));
+  StateHeader hd{};
+  hd.magic = kStateMagic;
+  hd.layer_size = (uint32_t)sizeof(LayerDev);
+  hd.n = h->n;
+  hd.step_index = h->step_index;
+  hd.next_batch = h->next_batch;
+  hd.good_steps = g.good_steps;
+  hd.shape_hash = shape_hash(h);
+  hd.config_hash = fnv1a(&h->hp, sizeof(h->hp));
+  std::memcpy(buf, &hd, sizeof(hd));
+  TA_HIP(hipMemcpy(static_cast<char*>(buf) + sizeof(hd), h->t.layers, (size_t)h->n * sizeof(LayerDev),
+                   hipMemcpyDeviceToHost));
+  return TRIACCEL_OK;
+}
+
+int triaccel_set_state(triaccel_handle h, const void* buf, int64_t size) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (!buf) return TRIACCEL_E_NULL_PTR;
+  if (size != triaccel_state_size(h)) return TRIACCEL_E_SHAPE_MISMATCH;
+  StateHeader hd;
+  std::memcpy(&hd, buf, sizeof(hd));
+  if (hd.magic != kStateMagic || hd.layer_size != sizeof(LayerDev)) return TRIACCEL_E_INVALID_ARG;
+  if (hd.n != h->n || hd.shape_hash != shape_hash(h)) return TRIACCEL_E_SHAPE_MISMATCH;
+  if (hd.config_hash != fnv1a(&h->hp, sizeof(h->hp))) return TRIACCEL_E_INVALID_ARG;
+  TA_HIP(hipStreamSynchronize(h->stream));
+  // the small global record starts clean (both parities of its per-step words are zero between steps)
+  GlobalDev g;
+  std::memset(&g, 0, sizeof(g));
+  g.good_steps = hd.good_steps;
+  TA_HIP(hipMemcpy(h->t.glob, &g, sizeof(g), hipMemcpyHostToDevice));
+  TA_HIP(hipMemcpy(h->t.layers, static_cast<const char*>(buf) + sizeof(hd), (size_t)h->n * sizeof(LayerDev),
+                   hipMemcpyHostToDevice));
+  h->step_index = hd.step_index;
+  h->next_batch = hd.next_batch;
+  std::memset(h->pinned_res, 0, sizeof(GlobalDev));
+  h->result_valid = false;
+  for (auto& s : h->ev_step) s = 0;  // stage timings of the other run do not apply
   return TRIACCEL_OK;
 }
 

@@ -99,6 +99,13 @@ class TriAccel:
         """[Gram pass, per-layer kernel, apply pass] in ms of the last power_iter call (profiling on)."""
         return B.triaccel_power_times_get(self.handle)
 
+    def get_state(self) -> bytes:
+        """The library's own state (per-layer records, counters); the tensors are saved by the caller."""
+        return B.triaccel_get_state(self.handle)
+
+    def set_state(self, blob: bytes) -> None:
+        B.triaccel_set_state(self.handle, blob)
+
     def param(self, i: int, code: int) -> torch.Tensor:
         """View of tensor ``i``'s stored parameters as precision ``code`` (take it from layer_state)."""
         return self.buf[i].view(_TORCH_DTYPE[code])[: self.numel[i]]

@@ -146,3 +146,43 @@ def test_memory_numbers_from_the_runtime_when_not_supplied():
     want = 112 if used < 0.7 * total else (80 if used > 0.9 * total else 96)
     assert res.next_batch_size == want
     opt.close()
+
+
+def test_state_round_trip_resumes_bit_identically():
+    wl = get_workload("resnet18")
+    n = wl.n_tensors
+    a = make(wl)
+    for t in range(1, 9):
+        a.step(*inputs(wl, t))
+    saved = snapshot(a)
+    blob = a.get_state()
+    assert len(blob) == ta.load_library().triaccel_state_size(a.handle)
+    for t in range(9, 15):
+        a.step(*inputs(wl, t))
+    want = snapshot(a)
+    want_layers = [(s.code, s.theta, s.v, s.eta, s.nnz) for s in a.layer_state()]
+    # a new handle, the caller's tensors restored, the library state restored
+    b = make(wl)
+    for i in range(n):
+        for dst, src in zip((b.buf[i], b.curv[i], b.mom[i], b.mask[i]), saved[i]):
+            dst.copy_(src)
+    b.set_state(blob)
+    with pytest.raises(ta.TriAccelError):
+        b.result()                                   # no step since the restore
+    for t in range(9, 15):
+        b.step(*inputs(wl, t))
+    assert b.result().step_index == 14
+    assert equal(want, snapshot(b))
+    assert want_layers == [(s.code, s.theta, s.v, s.eta, s.nnz) for s in b.layer_state()]
+    # blobs that do not belong to the handle are refused
+    lib = ta.load_library()
+    bad = bytearray(blob)
+    bad[0] ^= 1
+    assert lib.triaccel_set_state(b.handle, bytes(bad), len(bad)) == -1
+    assert lib.triaccel_set_state(b.handle, blob, len(blob) - 8) == -3
+    other = make(get_workload("tiny_mlp"))
+    assert lib.triaccel_set_state(other.handle, blob, len(blob)) == -3
+    c = ta.TriAccel(dict(wl.hyper, alpha=0.25), [wl.init_param(l).to(DEV) for l in range(n)], grad_dtype=wl.grad_dtype)
+    assert lib.triaccel_set_state(c.handle, blob, len(blob)) == -1     # other hyper-parameters
+    for o in (a, b, other, c):
+        o.close()

@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         "oracle_precision_code": (C.c_int, [f32, f32, f32, f32, f32]),
         "oracle_eta": (f32, [f32, f32, f32]),
         "oracle_update": (None, [vp, C.c_int, C.c_int, vp, C.c_int, vp, i64, f32, f32, f32, f32]),
+        "oracle_update_elementwise": (None, [vp, C.c_int, C.c_int, vp, C.c_int, vp, vp, vp, i64, f32, f32, f32, f32, f32]),
         "oracle_loss_scale_next": (f32, [f32, C.c_int, P(i32), f32, f32, i32]),
         "oracle_batch_next": (i32, [i32, u64, u64, f64, f64, i32, i32, i32, i32]),
         "oracle_power_step": (None, [vp, vp, vp, i64, i32, P(f64), P(f64), P(f64), P(u32)]),

@@ -41,6 +41,7 @@ class OracleConfig:
     b_min: int = 16
     b_max: int = 4096
     curvature_source: int = 0    # sample behind the diagonal EMA: 0 = Hutchinson pair z * Hz, 1 = squared gradient
+    elementwise_scale: int = 0   # 1: the step size is scaled per element by the masked |h_i| instead of per layer
     lambda_source: int = 0       # lambda_l of Sec. 3.2: 0 = largest kept |h_i| of the diagonal EMA,
                                  # 1 = largest |Rayleigh quotient| of the latched power iteration
 
@@ -155,9 +156,15 @@ class OracleTriAccel:
                                                  f32(cfg.tau_curv)))
         t.eta = f32(L.oracle_eta(f32(lr), f32(cfg.alpha), t.lam_ctrl))
         # update and store in the chosen precision
-        L.oracle_update(t.buf.ctypes.data, t.prev_code, t.code, g.ctypes.data, t.grad_dtype,
-                        None if t.mom is None else t.mom.ctypes.data, t.numel, inv_scale,
-                        f32(cfg.weight_decay), f32(cfg.momentum), t.eta)
+        if cfg.elementwise_scale == 1:
+            L.oracle_update_elementwise(t.buf.ctypes.data, t.prev_code, t.code, g.ctypes.data, t.grad_dtype,
+                                        None if t.mom is None else t.mom.ctypes.data, t.curv.ctypes.data,
+                                        t.mask.ctypes.data, t.numel, inv_scale, f32(cfg.weight_decay),
+                                        f32(cfg.momentum), f32(lr), f32(cfg.alpha))
+        else:
+            L.oracle_update(t.buf.ctypes.data, t.prev_code, t.code, g.ctypes.data, t.grad_dtype,
+                            None if t.mom is None else t.mom.ctypes.data, t.numel, inv_scale,
+                            f32(cfg.weight_decay), f32(cfg.momentum), t.eta)
 
     def power_step(self, us: Sequence[np.ndarray], hus: Sequence[np.ndarray], k: int, latch: bool) -> None:
         """One power iteration (Sec. 3.2) per tensor on k supplied pairs (u_j, H u_j); ``us[l]`` and

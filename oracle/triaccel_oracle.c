@@ -298,6 +298,42 @@ void oracle_update(void *param, int prev_code, int new_code, const void *g, int 
 }
 
 /* ------------------------------------------------------------------------ */
+/* Element-wise form of the step-size scaling (Sec. 3.2, fourth equation, applied
+ * per entry of the sparsified curvature instead of once per layer):
+ *   eta_i = eta_0 / (1 + alpha * a_i),   a_i = |h_i| if mask_i else 0,
+ * so that the mask acts on the update; with h constant over a fully masked layer it
+ * is the per-layer rule.  Everything else as in oracle_update.  fp32 per element:
+ *   den = fma(alpha, a_i, 1);  eta_i = lr / den;  theta' = fma(-eta_i, m, theta).   */
+/* ------------------------------------------------------------------------ */
+void oracle_update_elementwise(void *param, int prev_code, int new_code, const void *g, int grad_dtype,
+                               float *m, const float *h, const uint32_t *mask, int64_t n,
+                               float inv_scale, float wd, float mu, float lr, float alpha)
+{
+    float *next = (float *)malloc((size_t)n * sizeof(float));
+    for (int64_t i = 0; i < n; ++i) {
+        float th = widen(param, prev_code, i);
+        float gt = widen(g, grad_dtype, i) * inv_scale;
+        float d = fmaf(wd, th, gt);
+        float mm;
+        if (m) { m[i] = fmaf(mu, m[i], d); mm = m[i]; } else { mm = d; }
+        float a = ((mask[i >> 5] >> (i & 31)) & 1u) ? fabsf(h[i]) : 0.0f;
+        float den = fmaf(alpha, a, 1.0f);
+        float eta = lr / den;
+        next[i] = fmaf(-eta, mm, th);
+    }
+    if (new_code == ORC_FP32) {
+        memcpy(param, next, (size_t)n * sizeof(float));
+    } else if (new_code == ORC_BF16) {
+        uint16_t *p = (uint16_t *)param;
+        for (int64_t i = 0; i < n; ++i) p[i] = oracle_f32_to_bf16(next[i]);
+    } else {
+        uint16_t *p = (uint16_t *)param;
+        for (int64_t i = 0; i < n; ++i) p[i] = oracle_f32_to_f16(next[i]);
+    }
+    free(next);
+}
+
+/* ------------------------------------------------------------------------ */
 /* Dynamic loss scaling (prior art cited in Sec. 2): after a skipped step the
  * scale is multiplied by `backoff` and the count of good steps restarts; after
  * `growth_interval` consecutive good steps it is multiplied by `growth`.      */

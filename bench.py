@@ -34,10 +34,10 @@ MEASURED_TRAFFIC = {
 }
 
 
-def measured_traffic(workload, all_fp32, n_tensors_limit):
+def measured_traffic(workload, all_fp32, n_tensors_limit, variant=False):
     """Counter-measured HBM bytes per launch of k_update, or None if they do not apply to this run."""
     import hashlib
-    if workload != MEASURED_TRAFFIC["workload"] or all_fp32 or n_tensors_limit:
+    if workload != MEASURED_TRAFFIC["workload"] or all_fp32 or n_tensors_limit or variant:
         return None
     h = hashlib.sha256()
     for f in ("kernels.hip", "numerics.h", "common.h"):
@@ -48,7 +48,7 @@ def measured_traffic(workload, all_fp32, n_tensors_limit):
     return MEASURED_TRAFFIC["fetch_bytes"] + MEASURED_TRAFFIC["write_bytes"]
 
 
-def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False):
+def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False, elem=False):
     """Bytes each stage must move for one step, from the definitions of the stages:
     statistics read g; the EMA reads z, Hz, h and writes h; the mask pass re-reads h and writes one
     bit per element; the update reads g, the stored parameter and m, and writes the parameter and m."""
@@ -62,7 +62,8 @@ def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, m
             # the exact threshold needs |h| once more after the pass that creates it; that re-read is
             # part of the method's traffic whether or not the prediction lets the kernels skip it
             b["mask_fallback" if extra else "mask_in_ema"] += n * 4 + n / 8.0
-        upd = n * (grad_size + size(pc) + size(c) + (8 if momentum else 0))
+        # the element-wise form of the step size reads h once more in the update
+        upd = n * (grad_size + size(pc) + size(c) + (8 if momentum else 0) + (4 if elem else 0))
         b["update" if size(pc) == size(c) else "update_resize"] += upd
     return b
 
@@ -76,6 +77,8 @@ def main():
     ap.add_argument("--all-fp32", action="store_true", help="thresholds that keep every layer in FP32")
     ap.add_argument("--fisher", action="store_true",
                     help="curvature sample = squared gradient (no probe pairs) instead of the Hutchinson pair")
+    ap.add_argument("--elementwise", action="store_true",
+                    help="step size scaled per element by the masked |h_i| instead of per layer")
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -112,6 +115,8 @@ def main():
         hyper.update(tau_low=0.0, tau_high=0.0)
     if args.fisher:
         hyper.update(curvature_source=1)
+    if args.elementwise:
+        hyper.update(elementwise_scale=1)
     K, W = args.steps, args.warmup
     if args.mode == "power":
         return bench_power(args, wl, hyper, dev)
@@ -184,7 +189,7 @@ def main():
     switched = sum(1 for a, b in zip(codes_before, codes) if a != b)
     sel_passes = [s.sel_passes for s in state]
     alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, True, hyper["momentum"] != 0.0,
-                            fisher=args.fisher)
+                            fisher=args.fisher, elem=args.elementwise)
     total_bytes = sum(alg.values())
     # bytes each kernel stage actually has to move in the last timed step
     moved = {"grad_stats": alg["grad_stats"], "curv_ema": alg["curv_ema"] + alg["mask_in_ema"] / 33.0,
@@ -216,6 +221,7 @@ def main():
             "workload": f"{wl.name}: {L} tensors, {N} params, fp{8 * grad_size} gradients, probe every step, "
                         f"momentum {hyper['momentum']}, sparsity {hyper['sparsity_ppm'] / 1e4:.0f}%",
             "all_fp32": bool(args.all_fp32),
+            "step_size": "per element" if args.elementwise else "per layer",
             "curvature_source": "empirical Fisher (squared gradient)" if args.fisher else "Hutchinson pair (z, Hz)",
             "codes": {"fp16": codes.count(0), "bf16": codes.count(1), "fp32": codes.count(2)},
             "layers_switched_in_timed_region": switched,
@@ -230,7 +236,7 @@ def main():
             "unit": "GB/s",
             "frac": upd_gbps / HBM_PEAK_GBPS,
             "alg_bytes_per_launch": moved["update"],
-            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors),
+            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise),
         },
         "step": {
             "alg_bytes_per_param": total_bytes / N,

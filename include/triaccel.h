@@ -81,6 +81,10 @@ typedef struct {
   int32_t curvature_source; /* sample behind the diagonal curvature EMA ("Hessian or Fisher", Sec. 1 / 3.2):
                               0 = Hutchinson pair, u_i = z_i (Hz)_i / S (the caller supplies z and hz),
                               1 = empirical Fisher, u_i = (g_i / S)^2 (no probe; z and hz must be NULL)  */
+  int32_t elementwise_scale; /* 0 = one step size per layer, eta_l = eta_0 / (1 + alpha lambda_l) (Sec. 3.2);
+                              1 = the same rule applied per entry of the sparsified curvature,
+                              eta_i = eta_0 / (1 + alpha a_i), a_i = |h_i| for entries in the mask, else 0
+                              (lambda_l still drives the promotion rule); reads h once more in the update */
 } triaccel_config;
 
 /* One parameter tensor.  Contiguous, flat; numel elements. */

@@ -112,6 +112,7 @@ int validate_config(const triaccel_config* cfg) {
   if (cfg->lambda_source != 0 && cfg->lambda_source != 1) return TRIACCEL_E_INVALID_ARG;
   if (cfg->lambda_source == 1 && cfg->power_k == 0) return TRIACCEL_E_INVALID_ARG;
   if (cfg->curvature_source != 0 && cfg->curvature_source != 1) return TRIACCEL_E_INVALID_ARG;
+  if (cfg->elementwise_scale != 0 && cfg->elementwise_scale != 1) return TRIACCEL_E_INVALID_ARG;
   return TRIACCEL_OK;
 }
 
@@ -186,7 +187,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   c->hp = Hyper{config->beta_var,     config->beta_curv,     config->tau_low,       config->tau_high,
                 config->tau_curv,     config->alpha,         config->sparsity_ppm,  config->momentum,
                 config->weight_decay, config->ctrl_interval, config->scale_backoff, config->scale_growth,
-                config->growth_interval, config->lambda_source};
+                config->growth_interval, config->lambda_source, config->elementwise_scale};
   auto fail = [&](int code) {
     free_ctx(c);
     return code;
@@ -388,12 +389,18 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
     // most it can take; every launch leaves at once when no tensor is (still) in histogram mode
     for (int round = 0; round < 4; ++round) TA_HIP(launch_hist_pass(T, sc, s));
   }
+  const bool elem = h->cfg.elementwise_scale == 1;
+  if (elem && any_probe) {
+    // element-wise step sizes need the final threshold: finish the mask and the selection first
+    TA_HIP(launch_mask_pass(T, sc, s));
+    TA_HIP(launch_select_finish(T, sc, s));
+  }
   if (prof) TA_HIP(hipEventRecord(ev[4], s));
-  TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
   if (prof) TA_HIP(hipEventRecord(ev[5], s));
-  TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, s));
+  TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
   if (prof) TA_HIP(hipEventRecord(ev[6], s));
-  if (any_probe) TA_HIP(launch_select_finish(T, sc, s));
+  if (any_probe && !elem) TA_HIP(launch_select_finish(T, sc, s));
   if (prof) {
     TA_HIP(hipEventRecord(ev[7], s));
     h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;

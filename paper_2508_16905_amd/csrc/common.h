@@ -41,6 +41,7 @@ struct Hyper {
   float scale_backoff, scale_growth;
   int32_t growth_interval;
   int32_t lambda_source;  // 0: largest kept |h_i|; 1: latched power-iteration value
+  int32_t elementwise;    // 1: step size scaled per element by the masked |h_i|
 };
 
 // Per-step scalars handed to the kernels.
@@ -121,6 +122,7 @@ struct GlobalDev {
   int32_t good_steps;      // consecutive applied steps since the last loss-scale change
   uint32_t trans_count[2]; // number of tensors whose storage size changes (double-buffered by step parity)
   uint32_t hist_pending[2];// tensors still in histogram mode this step (same double buffering)
+  uint32_t mask_pending[2];// tensors whose mask the EMA kernel did not settle this step
   // result record
   int32_t res_skipped;
   float res_next_scale;

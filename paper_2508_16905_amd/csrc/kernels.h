@@ -31,8 +31,11 @@ hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float b
 hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
 hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s);
-hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
-hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s);
+hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha, bool elem,
+                         hipStream_t s);
+hipError_t launch_mask_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s);
+hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha,
+                                bool elem, hipStream_t s);
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s);
 
 }  // namespace triaccel

@@ -613,6 +613,7 @@ __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, Glo
     ls.k_rem = k;
     ls.passes = 1;
     ls.acc_above = 0;
+    if (outcome != 0) atomicAdd(&glob->mask_pending[step_id & 1u], 1u);
     if (outcome == 0) {
       ls.mode = kSelCand;
       ls.mask_done = 1;
@@ -1115,6 +1116,7 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
   if (l == 0) {
     glob->trans_count[(sc.step_id + 1u) & 1u] = 0;
     glob->hist_pending[(sc.step_id + 1u) & 1u] = 0;
+    glob->mask_pending[(sc.step_id + 1u) & 1u] = 0;
     float next = sc.loss_scale;
     if (skip) {
       glob->good_steps = 0;
@@ -1141,12 +1143,21 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
 //   store theta' in the layer's new precision, round to nearest even.
 // All loads of a chunk complete before its first store (needed when the storage size changes
 // in place, harmless otherwise).
+// ELEM: the step size is scaled per element instead of per layer (Sec. 3.2, "Step size scaling",
+// applied to each entry of the sparsified curvature): eta_i = lr / fma(alpha, a_i, 1) with
+// a_i = |h_i| if the entry is in the mask (|h_i| >= theta and |h_i| > 0), else 0; reads h once more.
 // ---------------------------------------------------------------------------------------------
-template <int GD, int PD, int ND, bool FULL, bool MOM>
+struct StepSize {
+  float neg_eta;       // per-layer form: -eta_l
+  float lr, alpha;     // element-wise form
+  uint32_t theta_key;  // element-wise form: bit pattern of the mask threshold
+};
+
+template <int GD, int PD, int ND, bool FULL, bool MOM, bool ELEM>
 __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base, float inv_scale, float wd, float mu,
-                                             float neg_eta, bool barrier) {
+                                             const StepSize& ss, bool barrier) {
   const int tid = threadIdx.x;
-  float g[kRows][4], th[kRows][4], m[kRows][4];
+  float g[kRows][4], th[kRows][4], m[kRows][4], h[ELEM ? kRows : 1][4];
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = base + r * kRowElems + tid * kVec;
@@ -1154,10 +1165,12 @@ __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base,
       load4<GD>(td.grad, idx, g[r]);
       load4<PD>(td.param, idx, th[r]);
       if (MOM) load4<kFP32>(td.mom, idx, m[r]);
+      if constexpr (ELEM) load4<kFP32>(td.curv, idx, h[r]);
     } else {
       load4_guard<GD>(td.grad, idx, td.numel, 0.0f, g[r]);
       load4_guard<PD>(td.param, idx, td.numel, 0.0f, th[r]);
       if (MOM) load4_guard<kFP32>(td.mom, idx, td.numel, 0.0f, m[r]);
+      if constexpr (ELEM) load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
     }
   }
 #pragma unroll
@@ -1168,6 +1181,13 @@ __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base,
       const float d = fmaf(wd, th[r][i], gt);
       const float mm = MOM ? fmaf(mu, m[r][i], d) : d;
       m[r][i] = mm;
+      float neg_eta = ss.neg_eta;
+      if constexpr (ELEM) {
+        const uint32_t key = f2u(h[r][i]) & 0x7fffffffu;
+        const float a = (key >= ss.theta_key && key != 0u) ? u2f(key) : 0.0f;
+        const float den = fmaf(ss.alpha, a, 1.0f);
+        neg_eta = -(ss.lr / den);
+      }
       th[r][i] = fmaf(neg_eta, mm, th[r][i]);
     }
   }
@@ -1185,48 +1205,74 @@ __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base,
   }
 }
 
-template <int GD, int PD, int ND>
+template <bool ELEM, int GD, int PD, int ND>
 __device__ __forceinline__ void update_dispatch2(const TensorDesc& td, int64_t base, float inv_scale, float wd,
-                                                 float mu, float neg_eta, bool barrier) {
+                                                 float mu, const StepSize& ss, bool barrier) {
   const bool full = base + kChunk <= td.numel;
   const bool mom = td.mom != nullptr;
   if (full) {
-    if (mom) update_chunk<GD, PD, ND, true, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
-    else update_chunk<GD, PD, ND, true, false>(td, base, inv_scale, wd, mu, neg_eta, barrier);
+    if (mom) update_chunk<GD, PD, ND, true, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
+    else update_chunk<GD, PD, ND, true, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
   } else {
-    if (mom) update_chunk<GD, PD, ND, false, true>(td, base, inv_scale, wd, mu, neg_eta, barrier);
-    else update_chunk<GD, PD, ND, false, false>(td, base, inv_scale, wd, mu, neg_eta, barrier);
+    if (mom) update_chunk<GD, PD, ND, false, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
+    else update_chunk<GD, PD, ND, false, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
   }
 }
 
-template <int GD, int PD>
+template <bool ELEM, int GD, int PD>
 __device__ __forceinline__ void update_dispatch1(int nd, const TensorDesc& td, int64_t base, float inv_scale,
-                                                 float wd, float mu, float neg_eta, bool barrier) {
+                                                 float wd, float mu, const StepSize& ss, bool barrier) {
   switch (nd) {
-    case kFP32: update_dispatch2<GD, PD, kFP32>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    case kBF16: update_dispatch2<GD, PD, kBF16>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    default: update_dispatch2<GD, PD, kFP16>(td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kFP32: update_dispatch2<ELEM, GD, PD, kFP32>(td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kBF16: update_dispatch2<ELEM, GD, PD, kBF16>(td, base, inv_scale, wd, mu, ss, barrier); break;
+    default: update_dispatch2<ELEM, GD, PD, kFP16>(td, base, inv_scale, wd, mu, ss, barrier); break;
   }
 }
 
-template <int GD>
+template <bool ELEM, int GD>
 __device__ __forceinline__ void update_dispatch0(int pd, int nd, const TensorDesc& td, int64_t base,
-                                                 float inv_scale, float wd, float mu, float neg_eta, bool barrier) {
+                                                 float inv_scale, float wd, float mu, const StepSize& ss,
+                                                 bool barrier) {
   switch (pd) {
-    case kFP32: update_dispatch1<GD, kFP32>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    case kBF16: update_dispatch1<GD, kBF16>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    default: update_dispatch1<GD, kFP16>(nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kFP32: update_dispatch1<ELEM, GD, kFP32>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kBF16: update_dispatch1<ELEM, GD, kBF16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    default: update_dispatch1<ELEM, GD, kFP16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
   }
 }
 
 // Gradient, old and new precision are uniform over a workgroup: branch once per chunk into a body
 // specialised for the combination.
+template <bool ELEM>
 __device__ __forceinline__ void update_any(const TensorDesc& td, int pd, int nd, int64_t base, float inv_scale,
-                                           float wd, float mu, float neg_eta, bool barrier) {
+                                           float wd, float mu, const StepSize& ss, bool barrier) {
   switch (td.grad_dtype) {
-    case kFP32: update_dispatch0<kFP32>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    case kBF16: update_dispatch0<kBF16>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
-    default: update_dispatch0<kFP16>(pd, nd, td, base, inv_scale, wd, mu, neg_eta, barrier); break;
+    case kFP32: update_dispatch0<ELEM, kFP32>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kBF16: update_dispatch0<ELEM, kBF16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    default: update_dispatch0<ELEM, kFP16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+  }
+}
+
+// Mask pass as a kernel of its own, for the element-wise form of the update, where the threshold
+// must be final before the update runs: the tensors whose mask the EMA kernel did not settle get
+// their mask written and their range keys listed here, before k_select_finish.  Leaves at once
+// when no tensor needs it (the steady state).
+__global__ __launch_bounds__(kThreads) void k_mask_pass(const TensorDesc* __restrict__ tds,
+                                                        const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
+                                                        const LayerDev* layers, const GlobalDev* glob, Candidate* cands,
+                                                        uint32_t* counters, StepScalars sc) {
+  if (step_skipped(glob, sc.step_id)) return;
+  if (glob->mask_pending[sc.step_id & 1u] == 0) return;
+  for (uint32_t c = blockIdx.x; c < total_chunks; c += gridDim.x) {
+    const ChunkRef cr = chunks[c];
+    const TensorDesc td = tds[cr.tensor];
+    const LayerDev& ls = layers[cr.tensor];
+    const uint32_t mode = ls.mode;
+    if (!td.has_probe || ls.mask_done || mode == kSelHist) continue;
+    const int64_t base = (int64_t)cr.index * kChunk;
+    if (base + kChunk <= td.numel)
+      mask_chunk<true>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
+    else
+      mask_chunk<false>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
   }
 }
 
@@ -1235,17 +1281,23 @@ __device__ __forceinline__ void update_any(const TensorDesc& td, int pd, int nd,
 // runs the fallback mask pass of its chunk when the tensor's mask was not settled by the EMA
 // kernel (nothing in the update depends on the mask, and a separate launch would cost a full
 // grid of idle workgroups on every step that needs no fallback).
+//
+// In the element-wise form (ELEM) the threshold must be final before the update, so the mask and
+// the listed keys are completed by the kernels before this one and no mask pass runs here.
+template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restrict__ tds,
                                                      const ChunkRef* __restrict__ chunks, LayerDev* layers,
                                                      const GlobalDev* glob, Candidate* cands, uint32_t* counters,
-                                                     StepScalars sc, float wd, float mu) {
+                                                     StepScalars sc, float wd, float mu, float alpha) {
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
   LayerDev& ls = layers[cr.tensor];
   const int pd = ls.prev_code, nd = ls.code;
   const TensorDesc td = tds[cr.tensor];
   const int64_t base = (int64_t)cr.index * kChunk;
-  if (elem_size(pd) == elem_size(nd)) update_any(td, pd, nd, base, sc.inv_scale, wd, mu, -ls.eta, false);
+  const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
+  if (elem_size(pd) == elem_size(nd)) update_any<ELEM>(td, pd, nd, base, sc.inv_scale, wd, mu, ss, false);
+  if constexpr (ELEM) return;
   // kSelHist cannot remain after the last scan; never write a mask from a stale range
   const uint32_t mode = ls.mode;
   if (td.has_probe && !ls.mask_done && mode != kSelHist) {
@@ -1263,10 +1315,12 @@ __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restric
 // write lands on bytes whose old contents were consumed by an earlier phase; widening runs them
 // in descending order for the same reason.  Launch `launch` of `n_launch` handles, for each
 // listed tensor, phase `launch` (narrowing) or `last_phase - launch` (widening).
+template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
                                                             const LayerDev* layers, const GlobalDev* glob,
                                                             const uint32_t* trans_list, uint32_t n_tensors,
-                                                            uint32_t launch, StepScalars sc, float wd, float mu) {
+                                                            uint32_t launch, StepScalars sc, float wd, float mu,
+                                                            float alpha) {
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t count = glob->trans_count[sc.step_id & 1u];
   const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
@@ -1282,8 +1336,9 @@ __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __
     const uint32_t phase = narrowing ? launch : last_phase - launch;
     const uint32_t c_lo = phase == 0 ? 0u : (1u << (phase - 1u));
     const uint32_t c_hi = phase == 0 ? 1u : min(1u << phase, td.n_chunks);
+    const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
     for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
-      update_any(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, -ls.eta, true);
+      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
   }
 }
 
@@ -1346,14 +1401,28 @@ hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hype
   return hipSuccess;
 }
 
-hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s) {
-  hipLaunchKernelGGL(k_update, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                     t.cands, t.cand_counters, sc, wd, mu);
+hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha, bool elem,
+                         hipStream_t s) {
+  if (elem)
+    hipLaunchKernelGGL(k_update<true>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
+                       t.cands, t.cand_counters, sc, wd, mu, alpha);
+  else
+    hipLaunchKernelGGL(k_update<false>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
+                       t.glob, t.cands, t.cand_counters, sc, wd, mu, alpha);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, hipStream_t s) {
+hipError_t launch_mask_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+  const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
+  hipLaunchKernelGGL(k_mask_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
+                     t.glob, t.cands, t.cand_counters, sc);
+  TA_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha,
+                                bool elem, hipStream_t s) {
   // phases 0 .. ceil(log2(max chunks per tensor)); a phase holds at most half the chunks of a tensor
   uint32_t last_phase = 0;
   while ((1u << last_phase) < t.max_chunks_per_tensor) ++last_phase;
@@ -1361,8 +1430,12 @@ hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, fl
   if (grid < 1) grid = 1;
   if (grid > t.fallback_grid) grid = t.fallback_grid;
   for (uint32_t launch = 0; launch <= last_phase; ++launch) {
-    hipLaunchKernelGGL(k_update_resize, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob, t.trans_list,
-                       t.n_tensors, launch, sc, wd, mu);
+    if (elem)
+      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
+    else
+      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
     TA_LAUNCH_CHECK();
   }
   return hipSuccess;

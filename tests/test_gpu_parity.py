@@ -237,3 +237,42 @@ def test_empirical_fisher_curvature_source(gd):
         p.gpu.step([x.to(p.device) for x in g], [x.to(p.device) for x in z], [x.to(p.device) for x in hz])
     p.compare("after the refused call")
     p.close()
+
+
+def test_elementwise_step_size_scaling():
+    # the step size is scaled per element by the masked |h_i|; steps without a probe reuse the
+    # last threshold; alpha large enough that masked and unmasked entries move visibly differently
+    sizes = [1, 33, 4096, 4097, 8193, 70001, 300007]
+    wl = custom(sizes, elementwise_scale=1, steps=10, alpha=50.0)
+    Pair(wl).run(10, probe_every=2).close()
+    for gd in (FP16, BF16):
+        wl = custom([4097, 100, 40000], grad_dtype=gd, loss_scale=1024.0, elementwise_scale=1, alpha=50.0)
+        Pair(wl).run(4).close()
+
+
+def test_elementwise_scaling_with_precision_switches_and_degenerate_curvature():
+    sizes = [9000, 4096, 130000, 50]
+    wl = custom(sizes, name="large_streaming", beta_var=0.0, tau_low=1e-4, tau_high=1e-2, tau_curv=1e30,
+                elementwise_scale=1, alpha=20.0)
+    p = Pair(wl)
+    mult = [0.1, 1.0, 10.0, 10.0, 0.1, 1.0, 0.1, 10.0]
+    for t, m in enumerate(mult, start=1):
+        g, z, hz = p.inputs(t)
+        if t == 4:
+            hz = [zz * 3.0 for zz in z]          # all magnitudes drift towards one value: many ties
+        if t == 6:
+            hz = [torch.zeros_like(h) for h in hz]
+        p.step([x * (m * 3.0) for x in g], z, hz)
+    assert {row[0] for row in p.code_hist} == {FP16, BF16, FP32}
+    p.close()
+
+
+def test_elementwise_scaling_with_the_fisher_source():
+    sizes = [33, 4097, 70001]
+    wl = custom(sizes, elementwise_scale=1, curvature_source=1, alpha=1e4, steps=6)
+    p = Pair(wl)
+    none = [None] * len(sizes)
+    for t in range(1, 7):
+        g, _, _ = p.inputs(t, probe=False)
+        p.step(g, none, none, update_curvature=(t != 4))
+    p.close()

@@ -9,7 +9,7 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtriaccel.so")
-SOURCES = ["kernels.hip", "power.hip", "api.hip"]
+SOURCES = ["kernels.hip", "update.hip", "update_resize.hip", "power.hip", "api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

@@ -4,38 +4,12 @@
 // lane holding 4 consecutive elements (one 128-bit access per lane, row and fp32 array).  All
 // arithmetic that decides a stored value is fp32 with an explicit operation order (fmaf where a
 // fused multiply-add is meant; the file is compiled with -ffp-contract=off); reductions are fp64.
-#include "kernels.h"
 
-#include <hip/hip_runtime.h>
 
-#include "numerics.h"
+
+#include "device_util.h"
 
 namespace triaccel {
-
-// ---------------------------------------------------------------------------------------------
-// wavefront (64 lanes) helpers
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor(v, o));
-  return v;
-}
-__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v |= (uint32_t)__shfl_xor(v, o);
-  return v;
-}
-
-__device__ __forceinline__ bool step_skipped(const GlobalDev* glob, uint32_t step_id) {
-  return *reinterpret_cast<const volatile uint32_t*>(&glob->skip_epoch) == step_id;
-}
-
-__device__ __forceinline__ uint32_t elem_size(int code) { return code == kFP32 ? 4u : 2u; }
 
 // (count, mean, M2) merge of two disjoint samples (Chan et al.), fp64.
 struct Moments {
@@ -189,105 +163,6 @@ __device__ __forceinline__ void flush_hist(uint32_t* s_hist, uint32_t bins, uint
   __syncthreads();
 }
 
-// Data-parallel-primitive moves inside the wavefront (no LDS traffic): swap neighbours in a quad,
-// swap the quad's halves, then mirror the 8-lane half row (lane i reads lane 7 - i; after the first
-// two steps all four lanes of a quad agree, so the mirror brings in the other quad's value).
-#define TA_DPP_OR(v, ctrl) ((v) | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), 0xF, 0xF, true))
-// Eight consecutive lanes hold the 32 elements of one mask word: combine their 4-bit nibbles.
-__device__ __forceinline__ uint32_t gather_mask_word(uint32_t nib, int lane) {
-  uint32_t v = nib << (4 * (lane & 7));
-  v = TA_DPP_OR(v, 0xB1);   // quad_perm [1, 0, 3, 2]
-  v = TA_DPP_OR(v, 0x4E);   // quad_perm [2, 3, 0, 1]
-  v = TA_DPP_OR(v, 0x141);  // row_half_mirror
-  return v;
-}
-
-// Store the kRows mask words of a chunk: lane (8j + r) of a wavefront writes row r's word j.
-template <bool FULL>
-__device__ __forceinline__ void store_mask_words(const TensorDesc& td, int64_t base, const uint32_t word[kRows]) {
-  const int tid = threadIdx.x;
-  const int sub = tid & 7;
-  if (sub < kRows) {
-    uint32_t v = word[0];
-#pragma unroll
-    for (int r = 1; r < kRows; ++r) v = (sub == r) ? word[r] : v;
-    const int64_t widx = ((base + (int64_t)sub * kRowElems) >> 5) + (tid >> 3);
-    if (FULL || widx < ((td.numel + 31) >> 5)) td.mask[widx] = v;
-  }
-}
-
-// Candidate storage.  Each tensor owns kCandLists sub-lists of sub_cap entries plus one overflow
-// list of cand_cap entries, each with its own counter in its own 128-byte line: appends from
-// different chunks and wavefronts go to different counters, because atomics on one hot address
-// serialise.  A batch that does not fit its sub-list spills into the overflow list, so nothing
-// is lost as long as the tensor lists at most cand_cap keys in total.
-__device__ __forceinline__ uint32_t* cand_counter(uint32_t* counters, uint32_t tensor, uint32_t list) {
-  return counters + ((size_t)tensor * (kCandLists + 1) + list) * kCandCounterStride;
-}
-
-__device__ __forceinline__ void reset_cand_counters(uint32_t* counters, uint32_t tensor) {
-  if (threadIdx.x <= kCandLists) *cand_counter(counters, tensor, threadIdx.x) = 0;
-}
-
-// Append a wavefront's candidates of one chunk (flag bit e of `flags` = element e of the lane's
-// 16) with one atomic per wavefront: lanes take consecutive slots by a prefix sum.  The sub-list
-// is chosen by (chunk, wavefront), so wavefronts running at the same time use different counters.
-__device__ __forceinline__ void append_candidates(uint32_t flags, const float (&h)[kRows][4], int64_t base,
-                                                  uint32_t chunk_index, uint32_t tensor, const TensorDesc& td,
-                                                  Candidate* cands, uint32_t* counters) {
-  if (!__any(flags != 0u)) return;  // uniform over the wavefront
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const uint32_t mine = __popc(flags);
-  uint32_t incl = mine;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t t = __shfl_up(incl, o);
-    if (lane >= o) incl += t;
-  }
-  const uint32_t total = __shfl(incl, kWave - 1);
-  const uint32_t list = (chunk_index * (kThreads / kWave) + wave) % kCandLists;
-  uint32_t start = 0, fit = 0, ostart = 0;
-  if (lane == 0) {
-    start = atomicAdd(cand_counter(counters, tensor, list), total);
-    fit = start < td.sub_cap ? min(total, td.sub_cap - start) : 0u;
-    if (fit < total) ostart = atomicAdd(cand_counter(counters, tensor, kCandLists), total - fit);
-  }
-  start = __shfl(start, 0);
-  fit = __shfl(fit, 0);
-  ostart = __shfl(ostart, 0);
-  uint32_t rank = incl - mine;
-  Candidate* lists = cands + td.cand_offset;
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (flags & (1u << (r * 4 + i))) {
-        const int64_t idx = base + r * kRowElems + threadIdx.x * kVec + i;
-        const Candidate c{(uint32_t)idx, f2u(h[r][i]) & 0x7fffffffu};
-        if (rank < fit) {
-          lists[(size_t)list * td.sub_cap + start + rank] = c;
-        } else {
-          const uint32_t o = ostart + (rank - fit);
-          if (o < td.cand_cap) lists[(size_t)kCandLists * td.sub_cap + o] = c;
-        }
-        ++rank;
-      }
-    }
-  }
-}
-
-// Visit every listed candidate of a tensor.  s_counts holds the kCandLists + 1 clamped counts.
-template <int NT, typename F>
-__device__ __forceinline__ void for_each_candidate(const TensorDesc& td, const Candidate* cands,
-                                                   const uint32_t* s_counts, F f) {
-  const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  for (uint32_t list = wave; list <= kCandLists; list += NT / kWave) {
-    const uint32_t cnt = s_counts[list];
-    const Candidate* p = cands + td.cand_offset + (size_t)list * td.sub_cap;
-    for (uint32_t j = lane; j < cnt; j += kWave) f(p[j]);
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Stage 2: curvature EMA (diagonal Hutchinson signal of Sec. 3.2), one workgroup per chunk.
 // Per element, fp32:  u = (z * hz) * inv_scale;  h = u on the tensor's first probe, else
@@ -306,7 +181,7 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
                                           uint32_t& nonfin) {
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  float z[kRows][4], hz[kRows][4], h[kRows][4];
+  float z[kRows][4], hz[SRC < 0 ? kRows : 1][4], h[kRows][4];
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = base + r * kRowElems + tid * kVec;
@@ -323,7 +198,7 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
       if (FULL) load4<SRC>(td.grad, idx, z[r]);
       else load4_guard<SRC>(td.grad, idx, td.numel, 0.0f, z[r]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) hz[r][i] = z[r][i] = z[r][i] * inv_scale;
+      for (int i = 0; i < 4; ++i) z[r][i] = z[r][i] * inv_scale;
     }
     if (FULL) load4<kFP32>(td.curv, idx, h[r]);
     else load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
@@ -336,8 +211,13 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
     uint32_t nib = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float u = z[r][i] * hz[r][i];
-      if constexpr (SRC < 0) u = u * inv_scale;
+      float u;
+      if constexpr (SRC < 0) {
+        u = z[r][i] * hz[r][i];
+        u = u * inv_scale;
+      } else {
+        u = z[r][i] * z[r][i];
+      }
       float hn = h[r][i];
       const bool valid = FULL || idx + i < td.numel;
       if ((f2u(u) & 0x7f800000u) == 0x7f800000u) {
@@ -796,46 +676,6 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fallback mask pass for tensors whose mask was not settled by the EMA kernel: re-reads |h| and
-// writes the bit mask.  Keys above the range are kept, keys below dropped; keys inside it are
-// listed and their bits are set afterwards by k_select_finish.  Called from k_update.
-// ---------------------------------------------------------------------------------------------
-template <bool FULL>
-__device__ __forceinline__ void mask_chunk(const TensorDesc& td, int64_t base, uint32_t mode, uint32_t theta,
-                                           uint32_t rng_lo, uint32_t rng_hi, uint32_t chunk_index,
-                                           uint32_t tensor, Candidate* cands, uint32_t* counters) {
-  const int tid = threadIdx.x;
-  const int lane = tid & (kWave - 1);
-  float h[kRows][4];
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
-    if (FULL) load4<kFP32>(td.curv, idx, h[r]);
-    else load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
-  }
-  uint32_t word[kRows];
-  uint32_t cflags = 0;
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    uint32_t nib = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t key = f2u(h[r][i]) & 0x7fffffffu;  // guarded fill 0: never kept, never listed
-      if (mode == kSelExact) {
-        if (key >= theta && key != 0u) nib |= 1u << i;
-      } else if (key >= rng_hi) {
-        nib |= 1u << i;
-      } else if (key != 0u && key >= rng_lo) {
-        cflags |= 1u << (r * 4 + i);
-      }
-    }
-    word[r] = gather_mask_word(nib, lane);
-  }
-  store_mask_words<FULL>(td, base, word);
-  append_candidates(cflags, h, base, chunk_index, tensor, td, cands, counters);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Finish: one workgroup per tensor resolves theta among the listed keys (radix select in LDS),
 // sets their mask bits, publishes theta / nnz and plans the next probed step: the band and the
 // fallback window are centred on the predicted threshold; their widths follow the error the
@@ -1137,233 +977,8 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 5: fused update + cast.  Per element, fp32:
-//   theta = widen(param);  gt = widen(g) * inv_scale;  d = fma(wd, theta, gt);
-//   m = fma(mu, m, d) (m = d without a buffer);  theta' = fma(-eta, m, theta);
-//   store theta' in the layer's new precision, round to nearest even.
-// All loads of a chunk complete before its first store (needed when the storage size changes
-// in place, harmless otherwise).
-// ELEM: the step size is scaled per element instead of per layer (Sec. 3.2, "Step size scaling",
-// applied to each entry of the sparsified curvature): eta_i = lr / fma(alpha, a_i, 1) with
-// a_i = |h_i| if the entry is in the mask (|h_i| >= theta and |h_i| > 0), else 0; reads h once more.
-// ---------------------------------------------------------------------------------------------
-struct StepSize {
-  float neg_eta;       // per-layer form: -eta_l
-  float lr, alpha;     // element-wise form
-  uint32_t theta_key;  // element-wise form: bit pattern of the mask threshold
-};
-
-template <int GD, int PD, int ND, bool FULL, bool MOM, bool ELEM>
-__device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base, float inv_scale, float wd, float mu,
-                                             const StepSize& ss, bool barrier) {
-  const int tid = threadIdx.x;
-  float g[kRows][4], th[kRows][4], m[kRows][4], h[ELEM ? kRows : 1][4];
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
-    if (FULL) {
-      load4<GD>(td.grad, idx, g[r]);
-      load4<PD>(td.param, idx, th[r]);
-      if (MOM) load4<kFP32>(td.mom, idx, m[r]);
-      if constexpr (ELEM) load4<kFP32>(td.curv, idx, h[r]);
-    } else {
-      load4_guard<GD>(td.grad, idx, td.numel, 0.0f, g[r]);
-      load4_guard<PD>(td.param, idx, td.numel, 0.0f, th[r]);
-      if (MOM) load4_guard<kFP32>(td.mom, idx, td.numel, 0.0f, m[r]);
-      if constexpr (ELEM) load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[r]);
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float gt = g[r][i] * inv_scale;
-      const float d = fmaf(wd, th[r][i], gt);
-      const float mm = MOM ? fmaf(mu, m[r][i], d) : d;
-      m[r][i] = mm;
-      float neg_eta = ss.neg_eta;
-      if constexpr (ELEM) {
-        const uint32_t key = f2u(h[r][i]) & 0x7fffffffu;
-        const float a = (key >= ss.theta_key && key != 0u) ? u2f(key) : 0.0f;
-        const float den = fmaf(ss.alpha, a, 1.0f);
-        neg_eta = -(ss.lr / den);
-      }
-      th[r][i] = fmaf(neg_eta, mm, th[r][i]);
-    }
-  }
-  if (barrier) __syncthreads();
-#pragma unroll
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t idx = base + r * kRowElems + tid * kVec;
-    if (FULL) {
-      store4<ND>(td.param, idx, th[r]);
-      if (MOM) store4<kFP32>(td.mom, idx, m[r]);
-    } else {
-      store4_guard<ND>(td.param, idx, td.numel, th[r]);
-      if (MOM) store4_guard<kFP32>(td.mom, idx, td.numel, m[r]);
-    }
-  }
-}
-
-template <bool ELEM, int GD, int PD, int ND>
-__device__ __forceinline__ void update_dispatch2(const TensorDesc& td, int64_t base, float inv_scale, float wd,
-                                                 float mu, const StepSize& ss, bool barrier) {
-  const bool full = base + kChunk <= td.numel;
-  const bool mom = td.mom != nullptr;
-  if (full) {
-    if (mom) update_chunk<GD, PD, ND, true, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-    else update_chunk<GD, PD, ND, true, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-  } else {
-    if (mom) update_chunk<GD, PD, ND, false, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-    else update_chunk<GD, PD, ND, false, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-  }
-}
-
-template <bool ELEM, int GD, int PD>
-__device__ __forceinline__ void update_dispatch1(int nd, const TensorDesc& td, int64_t base, float inv_scale,
-                                                 float wd, float mu, const StepSize& ss, bool barrier) {
-  switch (nd) {
-    case kFP32: update_dispatch2<ELEM, GD, PD, kFP32>(td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch2<ELEM, GD, PD, kBF16>(td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch2<ELEM, GD, PD, kFP16>(td, base, inv_scale, wd, mu, ss, barrier); break;
-  }
-}
-
-template <bool ELEM, int GD>
-__device__ __forceinline__ void update_dispatch0(int pd, int nd, const TensorDesc& td, int64_t base,
-                                                 float inv_scale, float wd, float mu, const StepSize& ss,
-                                                 bool barrier) {
-  switch (pd) {
-    case kFP32: update_dispatch1<ELEM, GD, kFP32>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch1<ELEM, GD, kBF16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch1<ELEM, GD, kFP16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-  }
-}
-
-// Gradient, old and new precision are uniform over a workgroup: branch once per chunk into a body
-// specialised for the combination.
-template <bool ELEM>
-__device__ __forceinline__ void update_any(const TensorDesc& td, int pd, int nd, int64_t base, float inv_scale,
-                                           float wd, float mu, const StepSize& ss, bool barrier) {
-  switch (td.grad_dtype) {
-    case kFP32: update_dispatch0<ELEM, kFP32>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch0<ELEM, kBF16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch0<ELEM, kFP16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-  }
-}
-
-// Mask pass as a kernel of its own, for the element-wise form of the update, where the threshold
-// must be final before the update runs: the tensors whose mask the EMA kernel did not settle get
-// their mask written and their range keys listed here, before k_select_finish.  Leaves at once
-// when no tensor needs it (the steady state).
-__global__ __launch_bounds__(kThreads) void k_mask_pass(const TensorDesc* __restrict__ tds,
-                                                        const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
-                                                        const LayerDev* layers, const GlobalDev* glob, Candidate* cands,
-                                                        uint32_t* counters, StepScalars sc) {
-  if (step_skipped(glob, sc.step_id)) return;
-  if (glob->mask_pending[sc.step_id & 1u] == 0) return;
-  for (uint32_t c = blockIdx.x; c < total_chunks; c += gridDim.x) {
-    const ChunkRef cr = chunks[c];
-    const TensorDesc td = tds[cr.tensor];
-    const LayerDev& ls = layers[cr.tensor];
-    const uint32_t mode = ls.mode;
-    if (!td.has_probe || ls.mask_done || mode == kSelHist) continue;
-    const int64_t base = (int64_t)cr.index * kChunk;
-    if (base + kChunk <= td.numel)
-      mask_chunk<true>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
-    else
-      mask_chunk<false>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
-  }
-}
-
-// Tensors whose storage size does not change: element i is read and written at the same address
-// by the same lane, so the update is in place.  One workgroup per chunk.  The same workgroup then
-// runs the fallback mask pass of its chunk when the tensor's mask was not settled by the EMA
-// kernel (nothing in the update depends on the mask, and a separate launch would cost a full
-// grid of idle workgroups on every step that needs no fallback).
-//
-// In the element-wise form (ELEM) the threshold must be final before the update, so the mask and
-// the listed keys are completed by the kernels before this one and no mask pass runs here.
-template <bool ELEM>
-__global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restrict__ tds,
-                                                     const ChunkRef* __restrict__ chunks, LayerDev* layers,
-                                                     const GlobalDev* glob, Candidate* cands, uint32_t* counters,
-                                                     StepScalars sc, float wd, float mu, float alpha) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const ChunkRef cr = chunks[blockIdx.x];
-  LayerDev& ls = layers[cr.tensor];
-  const int pd = ls.prev_code, nd = ls.code;
-  const TensorDesc td = tds[cr.tensor];
-  const int64_t base = (int64_t)cr.index * kChunk;
-  const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
-  if (elem_size(pd) == elem_size(nd)) update_any<ELEM>(td, pd, nd, base, sc.inv_scale, wd, mu, ss, false);
-  if constexpr (ELEM) return;
-  // kSelHist cannot remain after the last scan; never write a mask from a stale range
-  const uint32_t mode = ls.mode;
-  if (td.has_probe && !ls.mask_done && mode != kSelHist) {
-    if (base + kChunk <= td.numel)
-      mask_chunk<true>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
-    else
-      mask_chunk<false>(td, base, mode, ls.theta_key, ls.rng_lo, ls.rng_hi, cr.index, cr.tensor, cands, counters);
-  }
-}
-
-// Tensors whose storage size changes (2 <-> 4 bytes per element) are rewritten in place in
-// phases: phase 0 is chunk 0, phase p >= 1 the chunks [2^(p-1), 2^p).  Inside a phase the bytes
-// written (element range [lo, hi) at the new size) never overlap the bytes read (same range at
-// the old size) because hi <= 2 lo.  Narrowing runs the phases in ascending order, so every
-// write lands on bytes whose old contents were consumed by an earlier phase; widening runs them
-// in descending order for the same reason.  Launch `launch` of `n_launch` handles, for each
-// listed tensor, phase `launch` (narrowing) or `last_phase - launch` (widening).
-template <bool ELEM>
-__global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
-                                                            const LayerDev* layers, const GlobalDev* glob,
-                                                            const uint32_t* trans_list, uint32_t n_tensors,
-                                                            uint32_t launch, StepScalars sc, float wd, float mu,
-                                                            float alpha) {
-  if (step_skipped(glob, sc.step_id)) return;
-  const uint32_t count = glob->trans_count[sc.step_id & 1u];
-  const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
-  for (uint32_t i = 0; i < count; ++i) {
-    const uint32_t l = list[i];
-    const TensorDesc td = tds[l];
-    const LayerDev& ls = layers[l];
-    const int pd = ls.prev_code, nd = ls.code;
-    // number of phases: 1 + ceil(log2(n_chunks))
-    const uint32_t last_phase = td.n_chunks <= 1 ? 0u : 32u - (uint32_t)__clz(td.n_chunks - 1u);
-    if (launch > last_phase) continue;
-    const bool narrowing = elem_size(nd) < elem_size(pd);
-    const uint32_t phase = narrowing ? launch : last_phase - launch;
-    const uint32_t c_lo = phase == 0 ? 0u : (1u << (phase - 1u));
-    const uint32_t c_hi = phase == 0 ? 1u : min(1u << phase, td.n_chunks);
-    const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
-    for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
-      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Utility: fp32 -> {fp16, bf16, fp32} array conversion with the store path of the update kernel.
-// ---------------------------------------------------------------------------------------------
-template <int ND>
-__global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src, void* dst, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads * kVec;
-  for (int64_t idx = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * kVec; idx < n; idx += stride) {
-    float v[4];
-    load4_guard<kFP32>(src, idx, n, 0.0f, v);
-    store4_guard<ND>(dst, idx, n, v);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------------------------
-#define TA_LAUNCH_CHECK()                      \
-  do {                                         \
-    hipError_t e_ = hipGetLastError();         \
-    if (e_ != hipSuccess) return e_;           \
-  } while (0)
-
 hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
   hipLaunchKernelGGL(k_grad_stats, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.partials,
                      t.layers, t.glob, sc);
@@ -1397,59 +1012,6 @@ hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hi
 hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s) {
   hipLaunchKernelGGL(k_layer, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.partials, t.ema_partials,
                      t.cand_counters, t.layers, t.glob, t.trans_list, t.n_tensors, sc, hp);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
-hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha, bool elem,
-                         hipStream_t s) {
-  if (elem)
-    hipLaunchKernelGGL(k_update<true>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                       t.cands, t.cand_counters, sc, wd, mu, alpha);
-  else
-    hipLaunchKernelGGL(k_update<false>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
-                       t.glob, t.cands, t.cand_counters, sc, wd, mu, alpha);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
-hipError_t launch_mask_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
-  const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
-  hipLaunchKernelGGL(k_mask_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
-                     t.glob, t.cands, t.cand_counters, sc);
-  TA_LAUNCH_CHECK();
-  return hipSuccess;
-}
-
-hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha,
-                                bool elem, hipStream_t s) {
-  // phases 0 .. ceil(log2(max chunks per tensor)); a phase holds at most half the chunks of a tensor
-  uint32_t last_phase = 0;
-  while ((1u << last_phase) < t.max_chunks_per_tensor) ++last_phase;
-  uint32_t grid = (t.max_chunks_per_tensor + 1) / 2;
-  if (grid < 1) grid = 1;
-  if (grid > t.fallback_grid) grid = t.fallback_grid;
-  for (uint32_t launch = 0; launch <= last_phase; ++launch) {
-    if (elem)
-      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
-    else
-      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
-    TA_LAUNCH_CHECK();
-  }
-  return hipSuccess;
-}
-
-hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s) {
-  int64_t blocks = (n + kThreads * kVec - 1) / (kThreads * kVec);
-  if (blocks > 65536) blocks = 65536;
-  if (blocks < 1) blocks = 1;
-  switch (dtype) {
-    case kFP32: hipLaunchKernelGGL(k_cast<kFP32>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
-    case kBF16: hipLaunchKernelGGL(k_cast<kBF16>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
-    default: hipLaunchKernelGGL(k_cast<kFP16>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
-  }
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

@@ -1,0 +1,87 @@
+// gfx950 kernels: in-place update of tensors whose storage size changes (2 <-> 4 bytes per element),
+// and the stand-alone conversion utility.
+#include "update_body.h"
+
+namespace triaccel {
+
+// Tensors whose storage size changes (2 <-> 4 bytes per element) are rewritten in place in
+// phases: phase 0 is chunk 0, phase p >= 1 the chunks [2^(p-1), 2^p).  Inside a phase the bytes
+// written (element range [lo, hi) at the new size) never overlap the bytes read (same range at
+// the old size) because hi <= 2 lo.  Narrowing runs the phases in ascending order, so every
+// write lands on bytes whose old contents were consumed by an earlier phase; widening runs them
+// in descending order for the same reason.  Launch `launch` of `n_launch` handles, for each
+// listed tensor, phase `launch` (narrowing) or `last_phase - launch` (widening).
+template <bool ELEM>
+__global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
+                                                            const LayerDev* layers, const GlobalDev* glob,
+                                                            const uint32_t* trans_list, uint32_t n_tensors,
+                                                            uint32_t launch, StepScalars sc, float wd, float mu,
+                                                            float alpha) {
+  if (step_skipped(glob, sc.step_id)) return;
+  const uint32_t count = glob->trans_count[sc.step_id & 1u];
+  const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
+  for (uint32_t i = 0; i < count; ++i) {
+    const uint32_t l = list[i];
+    const TensorDesc td = tds[l];
+    const LayerDev& ls = layers[l];
+    const int pd = ls.prev_code, nd = ls.code;
+    // number of phases: 1 + ceil(log2(n_chunks))
+    const uint32_t last_phase = td.n_chunks <= 1 ? 0u : 32u - (uint32_t)__clz(td.n_chunks - 1u);
+    if (launch > last_phase) continue;
+    const bool narrowing = elem_size(nd) < elem_size(pd);
+    const uint32_t phase = narrowing ? launch : last_phase - launch;
+    const uint32_t c_lo = phase == 0 ? 0u : (1u << (phase - 1u));
+    const uint32_t c_hi = phase == 0 ? 1u : min(1u << phase, td.n_chunks);
+    const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
+    for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
+      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Utility: fp32 -> {fp16, bf16, fp32} array conversion with the store path of the update kernel.
+// ---------------------------------------------------------------------------------------------
+template <int ND>
+__global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src, void* dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads * kVec;
+  for (int64_t idx = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * kVec; idx < n; idx += stride) {
+    float v[4];
+    load4_guard<kFP32>(src, idx, n, 0.0f, v);
+    store4_guard<ND>(dst, idx, n, v);
+  }
+}
+
+hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha,
+                                bool elem, hipStream_t s) {
+  // phases 0 .. ceil(log2(max chunks per tensor)); a phase holds at most half the chunks of a tensor
+  uint32_t last_phase = 0;
+  while ((1u << last_phase) < t.max_chunks_per_tensor) ++last_phase;
+  uint32_t grid = (t.max_chunks_per_tensor + 1) / 2;
+  if (grid < 1) grid = 1;
+  if (grid > t.fallback_grid) grid = t.fallback_grid;
+  for (uint32_t launch = 0; launch <= last_phase; ++launch) {
+    if (elem)
+      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
+    else
+      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
+    TA_LAUNCH_CHECK();
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s) {
+  int64_t blocks = (n + kThreads * kVec - 1) / (kThreads * kVec);
+  if (blocks > 65536) blocks = 65536;
+  if (blocks < 1) blocks = 1;
+  switch (dtype) {
+    case kFP32: hipLaunchKernelGGL(k_cast<kFP32>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
+    case kBF16: hipLaunchKernelGGL(k_cast<kBF16>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
+    default: hipLaunchKernelGGL(k_cast<kFP16>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;
+  }
+  TA_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+}  // namespace triaccel

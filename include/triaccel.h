@@ -194,7 +194,20 @@ const char *triaccel_strerror(int code);
 /* Text of the last HIP failure on this thread ("" if none). */
 const char *triaccel_last_error(void);
 
-/* Record HIP events between the stages of every following step (on != 0) or stop doing so. */
+/*
+ * on != 0: the following triaccel_step calls replay the step as a HIP graph (captured at the first such
+ * call, one graph for steps that refresh the curvature and one for steps that do not) instead of
+ * launching its kernels one by one; results are identical.  Meant for small parameter sets, where the
+ * step is bound by launch overhead.  While profiling is on the kernels are launched one by one.
+ * The handle must have been created on a stream of its own (the default stream cannot be captured).
+ */
+int triaccel_set_graph(triaccel_handle h, int32_t on);
+
+/*
+ * Record HIP events in every following step: on = 1 at every stage boundary, on = 2 only around the
+ * update kernel (stage 4; the other stage times then read 0), on = 0 stop.  Every recorded event
+ * costs a few microseconds of the stream's time.
+ */
 int triaccel_set_profiling(triaccel_handle h, int32_t on);
 
 /*

@@ -30,6 +30,7 @@ from .binding import (  # noqa: F401
     triaccel_power_state,
     triaccel_power_times_get,
     triaccel_result,
+    triaccel_set_graph,
     triaccel_set_profiling,
     triaccel_stage_times_get,
     triaccel_step,

@@ -147,6 +147,7 @@ EXPORTS = {
     "triaccel_strerror": (C.c_char_p, [C.c_int]),
     "triaccel_last_error": (C.c_char_p, []),
     "triaccel_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
+    "triaccel_set_graph": (C.c_int, [C.c_void_p, C.c_int32]),
     "triaccel_stage_times_get": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(StageTimes)]),
     "triaccel_cast_f32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]),
     "triaccel_state_size": (C.c_int64, [C.c_void_p]),
@@ -242,8 +243,12 @@ def triaccel_strerror(code: int) -> str:
     return load_library().triaccel_strerror(code).decode()
 
 
-def triaccel_set_profiling(handle, on: bool) -> None:
+def triaccel_set_profiling(handle, on) -> None:
     _check(load_library().triaccel_set_profiling(handle, int(on)), "triaccel_set_profiling")
+
+
+def triaccel_set_graph(handle, on: bool) -> None:
+    _check(load_library().triaccel_set_graph(handle, int(on)), "triaccel_set_graph")
 
 
 def triaccel_stage_times_get(handle, steps_back: int = 0):

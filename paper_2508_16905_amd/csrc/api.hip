@@ -39,6 +39,12 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
+struct StepGraph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  hipGraphNode_t root = nullptr;  // the node that writes the per-step scalars
+};
+
 struct triaccel_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
@@ -59,11 +65,14 @@ struct triaccel_ctx {
   uint64_t step_index = 0;
   bool result_valid = false;  // a step has been enqueued since init / set_state
   int32_t next_batch = 0;
-  bool profiling = false;
+  int profiling = 0;  // 0 off, 1 every stage boundary, 2 only the boundaries of the update kernel
   hipEvent_t ev[TRIACCEL_PROFILE_RING][TRIACCEL_N_STAGES + 1] = {};
   uint64_t ev_step[TRIACCEL_PROFILE_RING] = {};  // step_index recorded in each ring slot (0 = none)
+  int ev_level[TRIACCEL_PROFILE_RING] = {};      // profiling level that slot was recorded with
   std::vector<LayerDev> layer_host;
   std::vector<void*> device_allocs;
+  bool use_graph = false;
+  StepGraph graphs[2];  // [0] steps without a curvature refresh, [1] with
   // power iteration (only with cfg.power_k > 0)
   PowerTables pt{};
   PowerDesc* power_staging[kRing] = {};
@@ -139,11 +148,101 @@ void free_ctx(triaccel_ctx* c) {
     if (c->power_ev[i]) (void)hipEventDestroy(c->power_ev[i]);
     if (c->power_prof[i]) (void)hipEventDestroy(c->power_prof[i]);
   }
+  for (auto& g : c->graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
   if (c->pinned_res) (void)hipHostFree(c->pinned_res);
   for (auto& set : c->ev)
     for (auto& e : set)
       if (e) (void)hipEventDestroy(e);
   delete c;
+}
+
+// The kernels of one optimizer step, in order, on the handle's stream.  `ev` (eight events) records
+// the stage boundaries.  Order of the stages: the per-layer assignment needs only the gradient
+// moments and lambda_l = max |h_i| (known after the EMA pass), so it runs before the threshold is
+// final; the mask is an output that nothing in the per-layer update depends on.
+int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t* ev, int level) {
+  const float beta_h = h->cfg.beta_curv;
+  const float omb_h = 1.0f - beta_h;
+  const DeviceTables& T = h->t;
+  hipStream_t s = h->stream;
+  const bool fisher = h->cfg.curvature_source == 1;
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[0], s));
+  TA_HIP(launch_grad_stats(T, sa, s));
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[1], s));
+  if (any_probe) TA_HIP(launch_curv_ema(T, sa, beta_h, omb_h, fisher ? 1 : 0, s));
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[2], s));
+  TA_HIP(launch_layer(T, sa, h->hp, s));
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[3], s));
+  if (any_probe) {
+    // fallback radix select: a predicted window that misses, then 11 + 11 + 9 key bits, is the
+    // most it can take; every launch leaves at once when no tensor is (still) in histogram mode
+    for (int round = 0; round < 4; ++round) TA_HIP(launch_hist_pass(T, sa, s));
+  }
+  const bool elem = h->cfg.elementwise_scale == 1;
+  if (elem && any_probe) {
+    // element-wise step sizes need the final threshold: finish the mask and the selection first
+    TA_HIP(launch_mask_pass(T, sa, s));
+    TA_HIP(launch_select_finish(T, sa, s));
+  }
+  if (ev) TA_HIP(hipEventRecord(ev[4], s));
+  TA_HIP(launch_update(T, sa, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
+  if (ev) TA_HIP(hipEventRecord(ev[5], s));
+  TA_HIP(launch_update_resize(T, sa, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[6], s));
+  if (any_probe && !elem) TA_HIP(launch_select_finish(T, sa, s));
+  if (ev && level == 1) TA_HIP(hipEventRecord(ev[7], s));
+  TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
+  return TRIACCEL_OK;
+}
+
+// Graph form of the same step: captured once per variant (with / without a curvature refresh)
+// from the launches above, with the kernels reading the per-step scalars from device memory; a
+// replay updates the one node that writes those scalars and launches the graph.
+int replay_step(triaccel_ctx* h, const StepScalars& sc, bool any_probe) {
+  StepGraph& g = h->graphs[any_probe ? 1 : 0];
+  hipStream_t s = h->stream;
+  if (!g.exec) {
+    hipGraph_t graph = nullptr;
+    TA_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    int rc = TRIACCEL_OK;
+    hipError_t e = launch_set_scalars(h->t, sc, s);
+    if (e != hipSuccess) rc = hip_fail(e, "launch_set_scalars");
+    if (!rc) rc = enqueue_step(h, StepArg{sc, h->t.scalars}, any_probe, nullptr, 0);
+    e = hipStreamEndCapture(s, &graph);  // always ends the capture, also after a failure above
+    if (rc) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return rc;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipStreamEndCapture");
+    size_t n_roots = 0;
+    hipGraphNode_t root = nullptr;
+    e = hipGraphGetRootNodes(graph, nullptr, &n_roots);
+    if (e == hipSuccess && n_roots == 1) e = hipGraphGetRootNodes(graph, &root, &n_roots);
+    if (e == hipSuccess && n_roots != 1) {
+      (void)hipGraphDestroy(graph);
+      g_last_error = "captured step graph does not start with a single node";
+      return TRIACCEL_E_HIP;
+    }
+    hipGraphExec_t exec = nullptr;
+    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+      (void)hipGraphDestroy(graph);
+      return hip_fail(e, "hipGraphInstantiate");
+    }
+    g.graph = graph;
+    g.exec = exec;
+    g.root = root;
+  }
+  hipKernelNodeParams params{};
+  void* args[2];
+  StepScalars* dst = h->t.scalars;
+  set_scalars_node_params(&params, args, &sc, &dst);
+  TA_HIP(hipGraphExecKernelNodeSetParams(g.exec, g.root, &params));
+  TA_HIP(hipGraphLaunch(g.exec, s));
+  return TRIACCEL_OK;
 }
 
 int32_t batch_rule(const triaccel_config& cfg, int32_t batch, uint64_t used, uint64_t total) {
@@ -251,6 +350,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   if ((rc = dev_alloc(c, &T.cands, (size_t)cand_total))) return fail(rc);
   if ((rc = dev_alloc(c, &T.cand_counters, (size_t)n * (kCandLists + 1) * kCandCounterStride))) return fail(rc);
   if ((rc = dev_alloc(c, &T.trans_list, (size_t)n * 2))) return fail(rc);
+  if ((rc = dev_alloc(c, &T.scalars, 1))) return fail(rc);
   e = hipMemcpy(T.chunks, chunks.data(), chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(chunks)"));
   // shapes and chunk ranges are valid from now on; the pointers arrive with every step
@@ -366,47 +466,20 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   sc.loss_scale = args->loss_scale;
   sc.inv_scale = 1.0f / args->loss_scale;
   sc.step_id = (uint32_t)h->step_index;
-  const float beta_h = h->cfg.beta_curv;
-  const float omb_h = 1.0f - beta_h;
-  const DeviceTables& T = h->t;
-  hipStream_t s = h->stream;
-  const bool prof = h->profiling;
-  hipEvent_t* ev = h->ev[h->step_index % TRIACCEL_PROFILE_RING];
+  const bool prof = h->profiling != 0;
   h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = 0;
-
-  // Order of the stages.  The per-layer assignment needs only the gradient moments and
-  // lambda_l = max |h_i| (known after the EMA pass), so it runs before the threshold is final;
-  // the mask is an output that nothing in the update depends on.
-  if (prof) TA_HIP(hipEventRecord(ev[0], s));
-  TA_HIP(launch_grad_stats(T, sc, s));
-  if (prof) TA_HIP(hipEventRecord(ev[1], s));
-  if (any_probe) TA_HIP(launch_curv_ema(T, sc, beta_h, omb_h, fisher ? 1 : 0, s));
-  if (prof) TA_HIP(hipEventRecord(ev[2], s));
-  TA_HIP(launch_layer(T, sc, h->hp, s));
-  if (prof) TA_HIP(hipEventRecord(ev[3], s));
-  if (any_probe) {
-    // fallback radix select: a predicted window that misses, then 11 + 11 + 9 key bits, is the
-    // most it can take; every launch leaves at once when no tensor is (still) in histogram mode
-    for (int round = 0; round < 4; ++round) TA_HIP(launch_hist_pass(T, sc, s));
+  if (h->use_graph && !prof) {
+    const int rc = replay_step(h, sc, any_probe);
+    if (rc) return rc;
+  } else {
+    hipEvent_t* ev = prof ? h->ev[h->step_index % TRIACCEL_PROFILE_RING] : nullptr;
+    const int rc = enqueue_step(h, StepArg{sc, nullptr}, any_probe, ev, h->profiling);
+    if (rc) return rc;
+    if (prof) {
+      h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;
+      h->ev_level[h->step_index % TRIACCEL_PROFILE_RING] = h->profiling;
+    }
   }
-  const bool elem = h->cfg.elementwise_scale == 1;
-  if (elem && any_probe) {
-    // element-wise step sizes need the final threshold: finish the mask and the selection first
-    TA_HIP(launch_mask_pass(T, sc, s));
-    TA_HIP(launch_select_finish(T, sc, s));
-  }
-  if (prof) TA_HIP(hipEventRecord(ev[4], s));
-  TA_HIP(launch_update(T, sc, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
-  if (prof) TA_HIP(hipEventRecord(ev[5], s));
-  TA_HIP(launch_update_resize(T, sc, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
-  if (prof) TA_HIP(hipEventRecord(ev[6], s));
-  if (any_probe && !elem) TA_HIP(launch_select_finish(T, sc, s));
-  if (prof) {
-    TA_HIP(hipEventRecord(ev[7], s));
-    h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;
-  }
-  TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
-
   h->next_batch = next_batch;
   h->result_valid = true;
   return TRIACCEL_OK;
@@ -610,6 +683,16 @@ const char* triaccel_strerror(int code) {
 
 const char* triaccel_last_error(void) { return g_last_error.c_str(); }
 
+int triaccel_set_graph(triaccel_handle h, int32_t on) {
+  if (!h) return TRIACCEL_E_NOT_INITIALISED;
+  if (on && h->stream == nullptr) {
+    g_last_error = "graph replay needs a stream of its own: the default stream cannot be captured";
+    return TRIACCEL_E_HIP;
+  }
+  h->use_graph = on != 0;
+  return TRIACCEL_OK;
+}
+
 int triaccel_set_profiling(triaccel_handle h, int32_t on) {
   if (!h) return TRIACCEL_E_NOT_INITIALISED;
   if (on) {
@@ -617,7 +700,8 @@ int triaccel_set_profiling(triaccel_handle h, int32_t on) {
       for (auto& e : set)
         if (!e) TA_HIP(hipEventCreate(&e));
   }
-  h->profiling = on != 0;
+  if (on < 0 || on > 2) return TRIACCEL_E_INVALID_ARG;
+  h->profiling = on;
   return TRIACCEL_OK;
 }
 
@@ -630,8 +714,10 @@ int triaccel_stage_times_get(triaccel_handle h, int32_t steps_back, triaccel_sta
   const int slot = (int)(step % TRIACCEL_PROFILE_RING);
   if (h->ev_step[slot] != step) return TRIACCEL_E_NOT_INITIALISED;
   TA_HIP(hipStreamSynchronize(h->stream));
-  for (int i = 0; i < TRIACCEL_N_STAGES; ++i)
-    TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[slot][i], h->ev[slot][i + 1]));
+  for (int i = 0; i < TRIACCEL_N_STAGES; ++i) {
+    out->ms[i] = 0.0f;
+    if (h->ev_level[slot] == 1 || i == 4) TA_HIP(hipEventElapsedTime(&out->ms[i], h->ev[slot][i], h->ev[slot][i + 1]));
+  }
   return TRIACCEL_OK;
 }
 

@@ -52,6 +52,13 @@ struct StepScalars {
   uint32_t step_id;  // 1-based count of triaccel_step calls (wraps after 2^32)
 };
 
+// How a kernel receives them: by value (ordinary launch), or from device memory when `dev` is set
+// (a replayed graph, whose kernel arguments are frozen at capture).
+struct StepArg {
+  StepScalars value;
+  const StepScalars* dev;
+};
+
 // Device table, one entry per tensor; re-uploaded when a pointer changes.
 struct TensorDesc {
   void* param;

@@ -31,6 +31,8 @@ __device__ __forceinline__ bool step_skipped(const GlobalDev* glob, uint32_t ste
   return *reinterpret_cast<const volatile uint32_t*>(&glob->skip_epoch) == step_id;
 }
 
+__device__ __forceinline__ StepScalars step_scalars(const StepArg& sa) { return sa.dev ? *sa.dev : sa.value; }
+
 __device__ __forceinline__ uint32_t elem_size(int code) { return code == kFP32 ? 4u : 2u; }
 
 // Data-parallel-primitive moves inside the wavefront (no LDS traffic): swap neighbours in a quad,

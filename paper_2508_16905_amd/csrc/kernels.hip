@@ -77,7 +77,8 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __restrict__ tds,
                                                          const ChunkRef* __restrict__ chunks,
                                                          StatPartial* __restrict__ partials, LayerDev* layers,
-                                                         GlobalDev* glob, StepScalars sc) {
+                                                         GlobalDev* glob, StepArg sa) {
+  const StepScalars sc = step_scalars(sa);
   const ChunkRef cr = chunks[blockIdx.x];
   const TensorDesc td = tds[cr.tensor];
   const int64_t base = (int64_t)cr.index * kChunk;
@@ -259,8 +260,9 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
 __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restrict__ tds,
                                                        const ChunkRef* __restrict__ chunks, const LayerDev* layers,
                                                        const GlobalDev* glob, EmaPartial* __restrict__ ema_partials,
-                                                       Candidate* cands, uint32_t* counters, StepScalars sc,
+                                                       Candidate* cands, uint32_t* counters, StepArg sa,
                                                        float beta_h, float omb_h, int fisher) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
   const TensorDesc td = tds[cr.tensor];
@@ -609,7 +611,8 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
 __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
                                                         const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
                                                         LayerDev* layers, GlobalDev* glob, uint32_t* hist,
-                                                        StepScalars sc) {
+                                                        StepArg sa) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   if (__hip_atomic_load(&glob->hist_pending[sc.step_id & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
   __shared__ uint32_t s_hist[kHistBins];
@@ -698,7 +701,8 @@ __device__ __forceinline__ uint32_t finish_block_sum(uint32_t v, uint32_t* s_red
 __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDesc* __restrict__ tds,
                                                                   LayerDev* layers, const GlobalDev* glob,
                                                                   const Candidate* cands, uint32_t* counters,
-                                                                  StepScalars sc) {
+                                                                  StepArg sa) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
@@ -892,7 +896,8 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
                                                     const StatPartial* __restrict__ partials,
                                                     const EmaPartial* __restrict__ ema_partials, uint32_t* counters,
                                                     LayerDev* layers, GlobalDev* glob, uint32_t* trans_list,
-                                                    uint32_t n_tensors, StepScalars sc, Hyper hp) {
+                                                    uint32_t n_tensors, StepArg sa, Hyper hp) {
+  const StepScalars sc = step_scalars(sa);
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
   LayerDev& ls = layers[l];
@@ -979,39 +984,39 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
 // ---------------------------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------------------------
-hipError_t launch_grad_stats(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+hipError_t launch_grad_stats(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
   hipLaunchKernelGGL(k_grad_stats, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.partials,
-                     t.layers, t.glob, sc);
+                     t.layers, t.glob, sa);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_curv_ema(const DeviceTables& t, const StepScalars& sc, float beta_h, float omb_h, int fisher,
+hipError_t launch_curv_ema(const DeviceTables& t, const StepArg& sa, float beta_h, float omb_h, int fisher,
                            hipStream_t s) {
   hipLaunchKernelGGL(k_curv_ema, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                     t.ema_partials, t.cands, t.cand_counters, sc, beta_h, omb_h, fisher);
+                     t.ema_partials, t.cands, t.cand_counters, sa, beta_h, omb_h, fisher);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_hist_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+hipError_t launch_hist_pass(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
   const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_hist_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
-                     t.glob, t.hist, sc);
+                     t.glob, t.hist, sa);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_select_finish(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
   hipLaunchKernelGGL(k_select_finish, dim3(t.n_tensors), dim3(kFinishThreads), 0, s, t.tensors, t.layers, t.glob,
-                     t.cands, t.cand_counters, sc);
+                     t.cands, t.cand_counters, sa);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_layer(const DeviceTables& t, const StepScalars& sc, const Hyper& hp, hipStream_t s) {
+hipError_t launch_layer(const DeviceTables& t, const StepArg& sa, const Hyper& hp, hipStream_t s) {
   hipLaunchKernelGGL(k_layer, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.partials, t.ema_partials,
-                     t.cand_counters, t.layers, t.glob, t.trans_list, t.n_tensors, sc, hp);
+                     t.cand_counters, t.layers, t.glob, t.trans_list, t.n_tensors, sa, hp);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

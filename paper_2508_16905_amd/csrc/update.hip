@@ -12,7 +12,8 @@ namespace triaccel {
 __global__ __launch_bounds__(kThreads) void k_mask_pass(const TensorDesc* __restrict__ tds,
                                                         const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
                                                         const LayerDev* layers, const GlobalDev* glob, Candidate* cands,
-                                                        uint32_t* counters, StepScalars sc) {
+                                                        uint32_t* counters, StepArg sa) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   if (glob->mask_pending[sc.step_id & 1u] == 0) return;
   for (uint32_t c = blockIdx.x; c < total_chunks; c += gridDim.x) {
@@ -41,7 +42,8 @@ template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restrict__ tds,
                                                      const ChunkRef* __restrict__ chunks, LayerDev* layers,
                                                      const GlobalDev* glob, Candidate* cands, uint32_t* counters,
-                                                     StepScalars sc, float wd, float mu, float alpha) {
+                                                     StepArg sa, float wd, float mu, float alpha) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
   LayerDev& ls = layers[cr.tensor];
@@ -61,22 +63,22 @@ __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restric
   }
 }
 
-hipError_t launch_update(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha, bool elem,
+hipError_t launch_update(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha, bool elem,
                          hipStream_t s) {
   if (elem)
     hipLaunchKernelGGL(k_update<true>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                       t.cands, t.cand_counters, sc, wd, mu, alpha);
+                       t.cands, t.cand_counters, sa, wd, mu, alpha);
   else
     hipLaunchKernelGGL(k_update<false>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
-                       t.glob, t.cands, t.cand_counters, sc, wd, mu, alpha);
+                       t.glob, t.cands, t.cand_counters, sa, wd, mu, alpha);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_mask_pass(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+hipError_t launch_mask_pass(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
   const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_mask_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
-                     t.glob, t.cands, t.cand_counters, sc);
+                     t.glob, t.cands, t.cand_counters, sa);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

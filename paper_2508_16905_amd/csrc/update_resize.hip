@@ -15,8 +15,9 @@ template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
                                                             const LayerDev* layers, const GlobalDev* glob,
                                                             const uint32_t* trans_list, uint32_t n_tensors,
-                                                            uint32_t launch, StepScalars sc, float wd, float mu,
+                                                            uint32_t launch, StepArg sa, float wd, float mu,
                                                             float alpha) {
+  const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t count = glob->trans_count[sc.step_id & 1u];
   const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src
   }
 }
 
-hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, float wd, float mu, float alpha,
+hipError_t launch_update_resize(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha,
                                 bool elem, hipStream_t s) {
   // phases 0 .. ceil(log2(max chunks per tensor)); a phase holds at most half the chunks of a tensor
   uint32_t last_phase = 0;
@@ -62,13 +63,34 @@ hipError_t launch_update_resize(const DeviceTables& t, const StepScalars& sc, fl
   for (uint32_t launch = 0; launch <= last_phase; ++launch) {
     if (elem)
       hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
+                         t.trans_list, t.n_tensors, launch, sa, wd, mu, alpha);
     else
       hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sc, wd, mu, alpha);
+                         t.trans_list, t.n_tensors, launch, sa, wd, mu, alpha);
     TA_LAUNCH_CHECK();
   }
   return hipSuccess;
+}
+
+__global__ void k_set_scalars(StepScalars v, StepScalars* dst) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *dst = v;
+}
+
+hipError_t launch_set_scalars(const DeviceTables& t, const StepScalars& sc, hipStream_t s) {
+  hipLaunchKernelGGL(k_set_scalars, dim3(1), dim3(kWave), 0, s, sc, t.scalars);
+  TA_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+void set_scalars_node_params(hipKernelNodeParams* p, void** args, const StepScalars* sc, StepScalars* const* dst) {
+  args[0] = const_cast<StepScalars*>(sc);
+  args[1] = const_cast<StepScalars**>(dst);
+  p->func = reinterpret_cast<void*>(k_set_scalars);
+  p->gridDim = dim3(1);
+  p->blockDim = dim3(kWave);
+  p->sharedMemBytes = 0;
+  p->kernelParams = args;
+  p->extra = nullptr;
 }
 
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s) {

@@ -110,6 +110,10 @@ class TriAccel:
         """View of tensor ``i``'s stored parameters as precision ``code`` (take it from layer_state)."""
         return self.buf[i].view(_TORCH_DTYPE[code])[: self.numel[i]]
 
+    def set_graph(self, on: bool) -> None:
+        """Replay the step as a HIP graph instead of launching its kernels one by one."""
+        B.triaccel_set_graph(self.handle, on)
+
     def set_profiling(self, on: bool) -> None:
         B.triaccel_set_profiling(self.handle, on)
 

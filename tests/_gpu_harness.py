@@ -37,12 +37,17 @@ def same_or_both_nan(a: np.ndarray, b: np.ndarray) -> bool:
 
 
 class Pair:
-    def __init__(self, wl, workers=8, device="cuda:0"):
+    def __init__(self, wl, workers=8, device="cuda:0", graph=False):
+        """``graph``: the library replays the step as a HIP graph (needs a stream of its own)."""
         self.wl = wl
         self.device = torch.device(device)
         self.orc = make_oracle(wl, workers=workers)
         params = [wl.init_param(l).to(self.device) for l in range(wl.n_tensors)]
-        self.gpu = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype)
+        self.stream = torch.cuda.Stream(device=self.device) if graph else None
+        torch.cuda.synchronize()
+        self.gpu = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype, stream=self.stream)
+        if graph:
+            self.gpu.set_graph(True)
         self.scale = float(wl.hyper["loss_scale"])
         self.batch = int(wl.hyper["batch_size"])
         self.t = 0
@@ -70,6 +75,8 @@ class Pair:
         g_d = [g.to(dev) for g in grads]
         z_d = [None if z is None else z.to(dev) for z in zs]
         hz_d = [None if h is None else h.to(dev) for h in hzs]
+        if self.stream is not None:
+            torch.cuda.synchronize()  # the inputs were copied on the default stream
         self.gpu.step(g_d, z_d, hz_d, lr=lr, loss_scale=self.scale, batch_size=self.batch,
                       mem_used_bytes=mem[0], mem_total_bytes=mem[1], update_curvature=update_curvature)
         res_o = self.orc.step([to_numpy(g) for g in grads], [None if z is None else to_numpy(z) for z in zs],

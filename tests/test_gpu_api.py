@@ -94,6 +94,12 @@ def test_result_before_any_step_and_profiling_calls():
     opt.step(g, z, hz)
     times = opt.stage_times()
     assert len(times) == len(ta.STAGE_NAMES) and all(t >= 0 for t in times) and sum(times) > 0
+    assert times[0] > 0 and times[4] > 0
+    opt.set_profiling(2)              # only the update kernel is bracketed
+    opt.step(g, z, hz)
+    times = opt.stage_times()
+    assert times[4] > 0 and sum(times) == times[4]
+    assert lib.triaccel_set_profiling(opt.handle, 3) == -1
     opt.close()
 
 

@@ -9,14 +9,25 @@ namespace triaccel {
 // written (element range [lo, hi) at the new size) never overlap the bytes read (same range at
 // the old size) because hi <= 2 lo.  Narrowing runs the phases in ascending order, so every
 // write lands on bytes whose old contents were consumed by an earlier phase; widening runs them
-// in descending order for the same reason.  Launch `launch` of `n_launch` handles, for each
-// listed tensor, phase `launch` (narrowing) or `last_phase - launch` (widening).
+// in descending order for the same reason.
+//
+// The phases up to kSerialPhase (the first kSerialChunks chunks) are done by ONE workgroup per
+// tensor, chunk after chunk in the same order (ascending when narrowing, descending when
+// widening; every chunk loads, synchronises, then stores), in a single launch; each later phase
+// is a launch of its own.  With L = the last phase of the largest tensor there are
+// n_launch = 1 + max(0, L - kSerialPhase) launches:
+//   narrowing:  launch 0 = serial part, launch j >= 1 = phase kSerialPhase + j;
+//   widening:   launch j < n_launch - 1 = phase L - j, launch n_launch - 1 = serial part.
+// A tensor with fewer phases than the largest one skips the launches beyond its own.
+constexpr uint32_t kSerialPhase = 6;
+constexpr uint32_t kSerialChunks = 1u << kSerialPhase;  // 64 chunks = 262,144 elements
+
 template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
                                                             const LayerDev* layers, const GlobalDev* glob,
                                                             const uint32_t* trans_list, uint32_t n_tensors,
-                                                            uint32_t launch, StepArg sa, float wd, float mu,
-                                                            float alpha) {
+                                                            uint32_t launch, uint32_t n_launch, StepArg sa, float wd,
+                                                            float mu, float alpha) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t count = glob->trans_count[sc.step_id & 1u];
@@ -26,14 +37,24 @@ __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __
     const TensorDesc td = tds[l];
     const LayerDev& ls = layers[l];
     const int pd = ls.prev_code, nd = ls.code;
+    const bool narrowing = elem_size(nd) < elem_size(pd);
+    const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
+    const bool serial = narrowing ? launch == 0 : launch == n_launch - 1u;
+    if (serial) {
+      if (i % gridDim.x != blockIdx.x) continue;  // one workgroup per tensor
+      const uint32_t n_ser = min(kSerialChunks, td.n_chunks);
+      for (uint32_t q = 0; q < n_ser; ++q) {
+        const uint32_t c = narrowing ? q : n_ser - 1u - q;
+        update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
+      }
+      continue;
+    }
     // number of phases: 1 + ceil(log2(n_chunks))
     const uint32_t last_phase = td.n_chunks <= 1 ? 0u : 32u - (uint32_t)__clz(td.n_chunks - 1u);
-    if (launch > last_phase) continue;
-    const bool narrowing = elem_size(nd) < elem_size(pd);
-    const uint32_t phase = narrowing ? launch : last_phase - launch;
-    const uint32_t c_lo = phase == 0 ? 0u : (1u << (phase - 1u));
-    const uint32_t c_hi = phase == 0 ? 1u : min(1u << phase, td.n_chunks);
-    const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
+    const uint32_t phase = narrowing ? kSerialPhase + launch : kSerialPhase + (n_launch - 1u - launch);
+    if (phase > last_phase) continue;
+    const uint32_t c_lo = 1u << (phase - 1u);  // phase > kSerialPhase >= 1
+    const uint32_t c_hi = min(1u << phase, td.n_chunks);
     for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
       update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
   }
@@ -54,19 +75,20 @@ __global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src
 
 hipError_t launch_update_resize(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha,
                                 bool elem, hipStream_t s) {
-  // phases 0 .. ceil(log2(max chunks per tensor)); a phase holds at most half the chunks of a tensor
+  // last phase of the largest tensor: ceil(log2(chunks)); a phase holds at most half the chunks of a tensor
   uint32_t last_phase = 0;
   while ((1u << last_phase) < t.max_chunks_per_tensor) ++last_phase;
+  const uint32_t n_launch = 1u + (last_phase > kSerialPhase ? last_phase - kSerialPhase : 0u);
   uint32_t grid = (t.max_chunks_per_tensor + 1) / 2;
   if (grid < 1) grid = 1;
   if (grid > t.fallback_grid) grid = t.fallback_grid;
-  for (uint32_t launch = 0; launch <= last_phase; ++launch) {
+  for (uint32_t launch = 0; launch < n_launch; ++launch) {
     if (elem)
       hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sa, wd, mu, alpha);
+                         t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
     else
       hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, sa, wd, mu, alpha);
+                         t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
     TA_LAUNCH_CHECK();
   }
   return hipSuccess;

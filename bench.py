@@ -26,26 +26,43 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by what the same
 # counters read for the library's plain copy kernel: 2.000 and 1.000; see profiles/).  They belong
 # to the kernel sources with the digest below: when the sources differ, `traffic` is null.
+STEP_SOURCES = ("kernels.hip", "update.hip", "update_body.h", "device_util.h", "numerics.h", "common.h")
+POWER_SOURCES = ("power.hip", "power.h", "numerics.h", "common.h")
 MEASURED_TRAFFIC = {
-    "sources_sha256": "52b87dc61835d85e629f2881b6bd453e51bc931de4e50c5853ab32a188c0a9ca",
-    "workload": "large_streaming",
-    "fetch_bytes": 11.677e9,
-    "write_bytes": 7.348e9,
+    # k_update<false>, default run of the large_streaming workload
+    "step": {"sources_sha256": "1c268244dbcd5ef79c733f3e2c7907c64ca5a8c46bd6c9c986952b8dfc8538dd", "workload": "large_streaming",
+             "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
+    # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
+    "power": {"sources_sha256": "dacb33b548fab17214ea8c0ccb5b6132a89cff0eb91582cabbff05e35fc2dbf1", "workload": "large_streaming",
+              "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.48e9},
+              "k_power_gram": {"fetch_bytes": 42.95e9, "write_bytes": 0.01e9}},
 }
+
+
+def sources_digest(files):
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(ROOT, "paper_2508_16905_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
 
 
 def measured_traffic(workload, all_fp32, n_tensors_limit, variant=False):
     """Counter-measured HBM bytes per launch of k_update, or None if they do not apply to this run."""
-    import hashlib
-    if workload != MEASURED_TRAFFIC["workload"] or all_fp32 or n_tensors_limit or variant:
+    m = MEASURED_TRAFFIC["step"]
+    if workload != m["workload"] or all_fp32 or n_tensors_limit or variant:
         return None
-    h = hashlib.sha256()
-    for f in ("kernels.hip", "numerics.h", "common.h"):
-        with open(os.path.join(ROOT, "paper_2508_16905_amd", "csrc", f), "rb") as fh:
-            h.update(fh.read())
-    if h.hexdigest() != MEASURED_TRAFFIC["sources_sha256"]:
+    if sources_digest(STEP_SOURCES) != m["sources_sha256"]:
         return None
-    return MEASURED_TRAFFIC["fetch_bytes"] + MEASURED_TRAFFIC["write_bytes"]
+    return m["fetch_bytes"] + m["write_bytes"]
+
+
+def measured_power_traffic(workload, k, kernel, n_tensors_limit):
+    m = MEASURED_TRAFFIC["power"]
+    if workload != m["workload"] or k != 5 or n_tensors_limit or sources_digest(POWER_SOURCES) != m["sources_sha256"]:
+        return None
+    return m[kernel]["fetch_bytes"] + m[kernel]["write_bytes"]
 
 
 def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False, elem=False):
@@ -322,7 +339,8 @@ def bench_power(args, wl, hyper, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {L} tensors, {N} params, one power iteration on k = {k} fp32 vectors per tensor"},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": dom[2], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dom[2] / HBM_PEAK_GBPS, "alg_bytes_per_launch": pass_bytes, "traffic": None},
+                     "frac": dom[2] / HBM_PEAK_GBPS, "alg_bytes_per_launch": pass_bytes,
+                     "traffic": measured_power_traffic(wl.name, k, dom[0], args.tensors)},
         "step": {"alg_bytes_per_param": 16.0 * k, "alg_GB": 2 * pass_bytes / 1e9,
                  "GBps": 2 * pass_bytes / 1e9 / (ms / 1e3), "frac_of_peak": 2 * pass_bytes / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS},
         "stages": {"gram": {"ms": round(stage[0], 4), "GBps": round(gram_gbps, 1)}, "layer": {"ms": round(stage[1], 4)},

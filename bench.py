@@ -113,8 +113,8 @@ def main():
                     help="also run the library's plain fp32 copy kernel on 1 GiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the step shards by whole tensors, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(a sharded job would run one such step per rank on its own tensors)", file=sys.stderr)
         sys.exit(2)
     if args.steps < 1 or args.steps > 63:
         print("bench.py: --steps must be in 1..63 (stage timings are kept for the last 64 steps)", file=sys.stderr)
@@ -387,12 +387,19 @@ def cpu_baseline(wl, hyper, first_set, n_sample, scale):
     orc.step(g, z, hz, float(hyper["lr"]), scale, int(hyper["batch_size"]), 8, 10)
     dt = time.perf_counter() - t0
     n = sum(wl.numel(l) for l in idx)
+    # the same oracle on one thread, first tensor only
+    one = oracle.OracleTriAccel(cfg, [params[0]], [wl.init_dtype(idx[0])], [wl.grad_dtype], workers=1)
+    t0 = time.perf_counter()
+    one.step(g[:1], z[:1], hz[:1], float(hyper["lr"]), scale, int(hyper["batch_size"]), 8, 10)
+    dt1 = time.perf_counter() - t0
     return {
         "value": n / dt,
         "unit": "params/s",
         "cores": cores,
         "kind": "oracle",
         "sample": f"first {len(idx)} tensors ({n} params) of the workload, 1 step, {dt:.2f} s wall",
+        "single_thread_value": wl.numel(idx[0]) / dt1,
+        "single_thread_sample": f"first tensor ({wl.numel(idx[0])} params), 1 step, {dt1:.2f} s wall",
     }
 
 

@@ -36,7 +36,7 @@ def check_properties(opt, l, st, k):
     assert st.lambda_ == float(a.max().item())
 
 
-def run_sampled(wl, sample, steps, dev, check_all_every=1):
+def run_sampled(wl, sample, steps, dev, check_all_every=1, fisher=False):
     L = wl.n_tensors
     params = [wl.init_param(l, device=dev) for l in range(L)]
     opt = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype)
@@ -48,16 +48,19 @@ def run_sampled(wl, sample, steps, dev, check_all_every=1):
     skipped_steps = []
     for t in range(1, steps + 1):
         grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
-        pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
-        zs, hzs = [p[0] for p in pr], [p[1] for p in pr]
-        del pr
+        if fisher:
+            zs = hzs = [None] * L
+        else:
+            pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
+            zs, hzs = [p[0] for p in pr], [p[1] for p in pr]
+            del pr
         opt.step(grads, zs, hzs, lr=wl.hyper["lr"], loss_scale=scale, batch_size=batch, mem_used_bytes=8,
                  mem_total_bytes=10)
         res = opt.result()
         # overflow in tensors the oracle does not hold, found with a library reduction
         elsewhere = any((not bool(torch.isfinite(grads[l]).all())) for l in range(L) if l not in sample)
-        ro = orc.step([to_numpy(grads[l]) for l in sample], [to_numpy(zs[l]) for l in sample],
-                      [to_numpy(hzs[l]) for l in sample], wl.hyper["lr"], scale, batch, 8, 10,
+        ro = orc.step([to_numpy(grads[l]) for l in sample], [None if fisher else to_numpy(zs[l]) for l in sample],
+                      [None if fisher else to_numpy(hzs[l]) for l in sample], wl.hyper["lr"], scale, batch, 8, 10,
                       overflow_elsewhere=elsewhere)
         assert res.skipped == ro["skipped"], (t, res.skipped, ro["skipped"])
         assert res.next_loss_scale == ro["next_loss_scale"] and res.next_batch_size == ro["next_batch_size"]
@@ -96,6 +99,13 @@ def test_large_streaming_full_size_sampled_tensors():
     assert wl.total_params == 1073741824
     skipped, codes = run_sampled(wl, sample=[0, 37, 63], steps=3, dev=torch.device("cuda:0"))
     assert skipped == [0, 0, 0] and len(set(codes)) >= 2
+
+
+def test_large_streaming_full_size_fisher_source_and_elementwise_step_size():
+    wl = get_workload("large_streaming")
+    wl.hyper = dict(wl.hyper, curvature_source=1, elementwise_scale=1, alpha=1e4)
+    skipped, codes = run_sampled(wl, sample=[11, 50], steps=3, dev=torch.device("cuda:0"), fisher=True)
+    assert skipped == [0, 0, 0]
 
 
 def test_mixed_state_full_size_sampled_tensors_with_overflow():

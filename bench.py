@@ -100,6 +100,9 @@ def main():
                     help="replay the step as a HIP graph in the timed region (stage times then come from "
                          "the same number of steps launched kernel by kernel afterwards)")
     ap.add_argument("--own-stream", action="store_true", help="run the steps on a stream of their own, not the default one")
+    ap.add_argument("--switch-stress", action="store_true",
+                    help="variance EMA off and a gradient scale cycling over three decades: every layer changes "
+                         "its storage precision at every step (all updates go through the in-place resize)")
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -138,6 +141,9 @@ def main():
         hyper.update(curvature_source=1)
     if args.elementwise:
         hyper.update(elementwise_scale=1)
+    if args.switch_stress:
+        hyper.update(beta_var=0.0, tau_curv=1e30)
+        args.input_sets = 6  # a multiple of the three-step cycle of the gradient scale
     K, W = args.steps, args.warmup
     if args.mode == "power":
         return bench_power(args, wl, hyper, dev)
@@ -155,8 +161,12 @@ def main():
     # generator steps to draw the input batches from (steps with injected inf/NaN are left out:
     # a skipped step does no work and would flatter the average)
     gen_steps = [t for t in range(1, 4 * R + 2) if not (wl.inject_every and t % wl.inject_every == 0)][:R]
-    for t in gen_steps:
+    for j, t in enumerate(gen_steps):
         grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
+        if args.switch_stress:
+            # unscaled standard deviation 0.0316 x {0.3, 3, 30}: variance below tau_low, between, above tau_high
+            for gten in grads:
+                gten.mul_((0.3, 3.0, 30.0)[j % 3])
         if args.fisher:
             sets.append((grads, None, None))
             continue
@@ -181,7 +191,7 @@ def main():
     if args.graph:
         opt.set_graph(True)
     else:
-        opt.set_profiling(2)
+        opt.set_profiling(1 if args.switch_stress else 2)
     lr = float(hyper["lr"])
 
     def one(i):
@@ -204,6 +214,7 @@ def main():
     res = opt.result()
     assert not res.skipped and res.step_index == W + K
     upd_ms_timed = None if args.graph else sum(opt.stage_times(back)[4] for back in range(K)) / K
+    resize_ms_timed = sum(opt.stage_times(back)[5] for back in range(K)) / K if args.switch_stress and not args.graph else None
     # stage breakdown: the same number of steps again, launched kernel by kernel with an event at
     # every stage boundary (not part of the timed region)
     opt.set_profiling(1)
@@ -237,6 +248,18 @@ def main():
         stages[name] = entry
     upd_ms = mean_ms["update"] if upd_ms_timed is None else upd_ms_timed
     upd_gbps = moved["update"] / 1e9 / (upd_ms / 1e3)
+    dominant, dominant_bytes = "k_update (fused update + cast)", moved["update"]
+    if args.switch_stress:
+        # every step of the cycle sends all tensors through one of the two kernels; report the in-place
+        # resize with its bytes and time averaged over the steps of the timed region
+        per_step = []
+        for back in range(K):
+            per_step.append(opt.stage_times(back))
+        dominant = "k_update_resize (in-place update while the storage size changes; all its launches of a step)"
+        upd_ms = mean_ms["update_resize"] if resize_ms_timed is None else resize_ms_timed
+        # two of the three steps of the cycle change the size: 2 -> 4 bytes and 4 -> 2 bytes per parameter
+        dominant_bytes = (2.0 / 3.0) * N * (grad_size + 6 + (8 if hyper["momentum"] != 0.0 else 0))
+        upd_gbps = dominant_bytes / 1e9 / (upd_ms / 1e3)
     step_gbps = total_bytes / 1e9 / (ms_per_step / 1e3)
 
     out = {
@@ -263,10 +286,11 @@ def main():
             "tensors_needing_extra_passes_over_h_last_step": sum(1 for x in sel_passes if x),
             "input_sets": R,
             "launch": "HIP graph replay" if args.graph else "kernel by kernel",
+            "switch_stress": bool(args.switch_stress),
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_update (fused update + cast)",
+            "kernel": dominant,
             "kernel_ms": upd_ms,
             "kernel_ms_from": "HIP events in the steps after the timed region (a graph replay carries none)"
                               if upd_ms_timed is None else "HIP events around the kernel in the timed region",
@@ -274,8 +298,8 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": upd_gbps / HBM_PEAK_GBPS,
-            "alg_bytes_per_launch": moved["update"],
-            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise),
+            "alg_bytes_per_launch": dominant_bytes,
+            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise or args.switch_stress),
         },
         "step": {
             "alg_bytes_per_param": total_bytes / N,

@@ -81,7 +81,7 @@ hipError_t launch_update_resize(const DeviceTables& t, const StepArg& sa, float 
   const uint32_t n_launch = 1u + (last_phase > kSerialPhase ? last_phase - kSerialPhase : 0u);
   uint32_t grid = (t.max_chunks_per_tensor + 1) / 2;
   if (grid < 1) grid = 1;
-  if (grid > t.fallback_grid) grid = t.fallback_grid;
+  if (grid > t.persistent_grid) grid = t.persistent_grid;
   for (uint32_t launch = 0; launch < n_launch; ++launch) {
     if (elem)
       hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,

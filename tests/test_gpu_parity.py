@@ -278,3 +278,41 @@ def test_elementwise_scaling_with_the_fisher_source():
         g, _, _ = p.inputs(t, probe=False)
         p.step(g, none, none, update_curvature=(t != 4))
     p.close()
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_seeded_random_configurations(seed):
+    """Random mixes of tensor sizes, gradient storage, initial precisions, curvature source, step-size
+    form, probe schedule and control interval, with an overflow injected once; every step compared."""
+    rs = np.random.default_rng(1000 + seed)
+    n_t = int(rs.integers(2, 7))
+    pool = [1, 2, 31, 33, 1000, 4095, 4096, 4097, 8191, 8192, 8193, 20000, 32769, 70001, 131072, 300007]
+    sizes = [int(rs.choice(pool)) for _ in range(n_t)]
+    gd = int(rs.choice([FP32, FP32, FP16, BF16]))
+    fisher = bool(rs.integers(0, 2))
+    hyper = dict(curvature_source=int(fisher), elementwise_scale=int(rs.integers(0, 2)),
+                 ctrl_interval=int(rs.choice([1, 1, 2, 3])), momentum=float(rs.choice([0.9, 0.0])),
+                 alpha=float(rs.choice([0.1, 10.0])), sparsity_ppm=int(rs.choice([500000, 900000, 990000])),
+                 growth_interval=3, loss_scale=1.0 if gd == FP32 else 256.0,
+                 beta_var=float(rs.choice([0.9, 0.0])))
+    name = str(rs.choice(["resnet18", "large_streaming"]))
+    if hyper["beta_var"] == 0.0 and name == "large_streaming":
+        hyper.update(tau_low=1e-4, tau_high=1e-2)
+    wl = custom(sizes, name=name, grad_dtype=gd, param_dtypes=[int(rs.choice([FP16, BF16, FP32])) for _ in sizes],
+                steps=8, seed=500 + seed, **hyper)
+    p = Pair(wl)
+    probe_every = int(rs.choice([1, 1, 2]))
+    bad_step = int(rs.integers(2, 8))
+    mult = [0.3, 3.0, 30.0]
+    for t in range(1, 9):
+        probe = (t - 1) % probe_every == 0
+        g, z, hz = p.inputs(t, probe=probe and not fisher)
+        if hyper["beta_var"] == 0.0 and name == "large_streaming":
+            g = [x * mult[t % 3] for x in g]          # codes move between all three precisions
+        if t == bad_step:
+            victim = int(rs.integers(0, n_t))
+            g[victim] = g[victim].clone()
+            g[victim][int(rs.integers(0, sizes[victim]))] = float(rs.choice([np.inf, -np.inf, np.nan]))
+        res = p.step(g, z, hz, update_curvature=probe, label=f"seed {seed}")
+        assert res["skipped"] == int(t == bad_step)
+    p.close()

@@ -18,6 +18,7 @@ from workloads.configs import TORCH_DTYPE
 from _runner import make_oracle, to_numpy
 
 STAT_RTOL = 1e-5
+DECISION_MARGIN = 1e-4  # ten times the tolerance of the statistics
 
 
 def bits_equal(a: np.ndarray, b: np.ndarray) -> bool:
@@ -84,6 +85,14 @@ class Pair:
                               mem[0], mem[1], update_curvature=update_curvature)
         res_g = self.gpu.result()
         where = f"{wl.name} step {self.t} {label}"
+        if not res_o["skipped"]:
+            # decision stability: a reduction result within the statistics tolerance of a threshold could
+            # legitimately give another code; such an input is a flaw of the generated case, not of either side
+            for o in self.orc.tensors:
+                for tau in (wl.hyper["tau_low"], wl.hyper["tau_high"]):
+                    if tau > 0:
+                        margin = abs(float(o.v) - float(np.float32(tau))) / float(np.float32(tau))
+                        assert margin > DECISION_MARGIN, (where, "variance EMA too close to a threshold", float(o.v), tau)
         assert res_g.skipped == res_o["skipped"], where
         assert res_g.step_index == res_o["step_index"], where
         assert res_g.next_loss_scale == res_o["next_loss_scale"], where

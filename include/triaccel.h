@@ -85,6 +85,8 @@ typedef struct {
                               1 = the same rule applied per entry of the sparsified curvature,
                               eta_i = eta_0 / (1 + alpha a_i), a_i = |h_i| for entries in the mask, else 0
                               (lambda_l still drives the promotion rule); reads h once more in the update */
+  uint32_t topk_abs;       /* > 0: the mask keeps this many entries per layer (the paper's fixed top-k,
+                              Sec. 4.1: k = 5), clamped to [1, n_l]; 0: the fraction given by sparsity_ppm */
 } triaccel_config;
 
 /* One parameter tensor.  Contiguous, flat; numel elements. */

@@ -53,6 +53,7 @@ def lib() -> C.CDLL:
         "oracle_fisher_ema": (None, [vp, C.c_int, vp, i64, f32, f32, C.c_int, P(u32)]),
         "oracle_topk_count": (i64, [i64, u32]),
         "oracle_threshold_mask": (None, [vp, i64, u32, vp, P(f32), P(u32), P(f32)]),
+        "oracle_threshold_mask_k": (None, [vp, i64, i64, vp, P(f32), P(u32), P(f32)]),
         "oracle_precision_code": (C.c_int, [f32, f32, f32, f32, f32]),
         "oracle_eta": (f32, [f32, f32, f32]),
         "oracle_update": (None, [vp, C.c_int, C.c_int, vp, C.c_int, vp, i64, f32, f32, f32, f32]),

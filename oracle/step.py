@@ -28,6 +28,7 @@ class OracleConfig:
     tau_curv: float = 1.0        # Sec. 3.2 promotion threshold
     alpha: float = 0.1           # Sec. 3.2 step-size coefficient
     sparsity_ppm: int = 900000
+    topk_abs: int = 0            # > 0: keep this many entries per layer instead of a fraction (Sec. 4.1: k = 5)
     momentum: float = 0.9        # Sec. 4.1 baseline optimizer
     weight_decay: float = 5e-4
     ctrl_interval: int = 1       # T_ctrl, Sec. 3.4
@@ -143,8 +144,12 @@ class OracleTriAccel:
             t.curv_nonfinite = int(flag.value)
             t.probes_seen += 1
             theta, nnz, lam = C.c_float(), C.c_uint32(), C.c_float()
-            L.oracle_threshold_mask(t.curv.ctypes.data, t.numel, cfg.sparsity_ppm, t.mask.ctypes.data,
-                                    C.byref(theta), C.byref(nnz), C.byref(lam))
+            if cfg.topk_abs > 0:
+                L.oracle_threshold_mask_k(t.curv.ctypes.data, t.numel, int(cfg.topk_abs), t.mask.ctypes.data,
+                                          C.byref(theta), C.byref(nnz), C.byref(lam))
+            else:
+                L.oracle_threshold_mask(t.curv.ctypes.data, t.numel, cfg.sparsity_ppm, t.mask.ctypes.data,
+                                        C.byref(theta), C.byref(nnz), C.byref(lam))
             t.theta, t.nnz, t.lam = f32(theta.value), int(nnz.value), f32(lam.value)
         if cfg.lambda_source == 1:
             t.lam = t.lam_power

@@ -211,12 +211,24 @@ int64_t oracle_topk_count(int64_t n, uint32_t s_ppm)
     return k;
 }
 
+/* The same with the number of kept entries given directly (the paper's "top-k" with a fixed k,
+ * Sec. 4.1: k = 5), clamped to [1, n]. */
+void oracle_threshold_mask_k(const float *h, int64_t n, int64_t k, uint32_t *mask,
+                             float *theta_out, uint32_t *nnz_out, float *lambda_out);
+
 void oracle_threshold_mask(const float *h, int64_t n, uint32_t s_ppm, uint32_t *mask,
                            float *theta_out, uint32_t *nnz_out, float *lambda_out)
 {
+    oracle_threshold_mask_k(h, n, oracle_topk_count(n, s_ppm), mask, theta_out, nnz_out, lambda_out);
+}
+
+void oracle_threshold_mask_k(const float *h, int64_t n, int64_t k, uint32_t *mask,
+                             float *theta_out, uint32_t *nnz_out, float *lambda_out)
+{
     uint32_t *a = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
     for (int64_t i = 0; i < n; ++i) a[i] = bits_of(h[i]) & 0x7fffffffu;
-    int64_t k = oracle_topk_count(n, s_ppm);
+    if (k < 1) k = 1;
+    if (k > n) k = n;
     uint32_t *sorted = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
     memcpy(sorted, a, (size_t)n * sizeof(uint32_t));
     qsort(sorted, (size_t)n, sizeof(uint32_t), cmp_desc_u32);

@@ -46,9 +46,10 @@ class Config(C.Structure):
         ("lambda_source", C.c_int32),
         ("curvature_source", C.c_int32),
         ("elementwise_scale", C.c_int32),
+        ("topk_abs", C.c_uint32),
     ]
     # fields a hyper-parameter dict may leave out
-    _OPTIONAL = {"power_k": 0, "lambda_source": 0, "curvature_source": 0, "elementwise_scale": 0}
+    _OPTIONAL = {"power_k": 0, "lambda_source": 0, "curvature_source": 0, "elementwise_scale": 0, "topk_abs": 0}
 
     @classmethod
     def from_hyper(cls, hyper: dict) -> "Config":

@@ -286,7 +286,8 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   c->hp = Hyper{config->beta_var,     config->beta_curv,     config->tau_low,       config->tau_high,
                 config->tau_curv,     config->alpha,         config->sparsity_ppm,  config->momentum,
                 config->weight_decay, config->ctrl_interval, config->scale_backoff, config->scale_growth,
-                config->growth_interval, config->lambda_source, config->elementwise_scale};
+                config->growth_interval, config->lambda_source, config->elementwise_scale,
+                config->topk_abs};
   auto fail = [&](int code) {
     free_ctx(c);
     return code;

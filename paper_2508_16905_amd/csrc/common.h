@@ -42,6 +42,7 @@ struct Hyper {
   int32_t growth_interval;
   int32_t lambda_source;  // 0: largest kept |h_i|; 1: latched power-iteration value
   int32_t elementwise;    // 1: step size scaled per element by the masked |h_i|
+  uint32_t topk_abs;      // > 0: entries kept per layer (instead of the fraction sparsity_ppm)
 };
 
 // Per-step scalars handed to the kernels.

@@ -422,9 +422,10 @@ __device__ BinHit find_rank_from_top(const uint32_t* s_hist, uint32_t bins, uint
   return hit;
 }
 
-__device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm) {
-  // k = n - floor(n * s / 1e6), clamped to [1, n]; n < 2^31 so the product fits 64 bits
-  int64_t k = n - (int64_t)(((uint64_t)n * (uint64_t)s_ppm) / 1000000ull);
+__device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm, uint32_t k_abs) {
+  // a fixed k if given, else k = n - floor(n * s / 1e6); clamped to [1, n]; n < 2^31 so the
+  // product fits 64 bits
+  int64_t k = k_abs ? (int64_t)k_abs : n - (int64_t)(((uint64_t)n * (uint64_t)s_ppm) / 1000000ull);
   if (k < 1) k = 1;
   if (k > n) k = n;
   return (uint32_t)k;
@@ -437,7 +438,7 @@ __device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm) {
 // ---------------------------------------------------------------------------------------------
 __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob,
                              const EmaPartial* __restrict__ ema_partials, uint32_t* counters, uint32_t step_id,
-                             uint32_t sparsity_ppm, uint32_t (*s_red)[kThreads / kWave]) {
+                             uint32_t sparsity_ppm, uint32_t topk_abs, uint32_t (*s_red)[kThreads / kWave]) {
   uint32_t above = 0, zeros = 0, maxkey = 0, nonfin = 0, listed = 0;
   for (uint32_t c = threadIdx.x; c < td.n_chunks; c += kThreads) {
     const EmaPartial p = ema_partials[td.first_chunk + c];
@@ -471,7 +472,7 @@ __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, Glo
     listed += s_red[4][w];
   }
   const uint32_t nonzero = (uint32_t)td.numel - zeros;
-  const uint32_t k = topk_count(td.numel, sparsity_ppm);
+  const uint32_t k = topk_count(td.numel, sparsity_ppm, topk_abs);
   // 0: the lists settle it; 1: theta = 0 (fewer non-zero keys than k); 2: histogram passes
   int outcome;
   if (td.list_all) outcome = 0;
@@ -904,7 +905,7 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
   const bool skip = step_skipped(glob, sc.step_id);
   __shared__ Moments s_m[kThreads / kWave];
   __shared__ uint32_t s_red[5][kThreads / kWave];
-  if (!skip && td.has_probe) select_begin(l, td, ls, glob, ema_partials, counters, sc.step_id, hp.sparsity_ppm, s_red);
+  if (!skip && td.has_probe) select_begin(l, td, ls, glob, ema_partials, counters, sc.step_id, hp.sparsity_ppm, hp.topk_abs, s_red);
   Moments mom{0.0, 0.0, 0.0};
   if (!skip) {
     // fixed merge order: each thread folds a contiguous run of chunk partials, then a tree

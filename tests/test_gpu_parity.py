@@ -316,3 +316,14 @@ def test_seeded_random_configurations(seed):
         res = p.step(g, z, hz, update_curvature=probe, label=f"seed {seed}")
         assert res["skipped"] == int(t == bad_step)
     p.close()
+
+
+def test_fixed_top_k_instead_of_a_fraction():
+    # the paper's k = 5 (Sec. 4.1): the mask keeps the five largest magnitudes of every layer (fewer
+    # elements than that: all non-zero ones); also a k beyond the list capacity of a small tensor
+    sizes = [1, 3, 5, 6, 4096, 4097, 70001, 300007]
+    for k in (5, 3000):
+        wl = custom(sizes, topk_abs=k, steps=8)
+        p = Pair(wl).run(8)
+        assert [t.nnz for t in p.orc.tensors] == [min(k, n) for n in sizes]
+        p.close()

@@ -87,3 +87,34 @@ def test_invariants_and_numpy_partition(n, s_ppm):
     assert np.count_nonzero(a > theta) < k
     assert nnz >= min(k, np.count_nonzero(a > 0))
     assert lam == (float(a.max()) if nnz else 0.0)
+
+
+def select_k(h, k):
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    mask = np.zeros((h.size + 31) // 32, np.uint32)
+    theta, nnz, lam = C.c_float(), C.c_uint32(), C.c_float()
+    oracle.lib().oracle_threshold_mask_k(h.ctypes.data, h.size, k, mask.ctypes.data, C.byref(theta), C.byref(nnz),
+                                         C.byref(lam))
+    bitsv = np.unpackbits(mask.view(np.uint8), bitorder="little")[: h.size].astype(bool)
+    return theta.value, nnz.value, lam.value, bitsv
+
+
+def test_fixed_k_keeps_the_k_largest_magnitudes():
+    # the paper's top-k with k = 5 (Sec. 4.1): threshold = fifth largest magnitude
+    h = np.array([0.5, -9.0, 3.0, 7.5, -1.0, 0.0, 2.0, -4.0, 6.0, 0.25], np.float32)
+    theta, nnz, lam, b = select_k(h, 5)
+    assert (theta, nnz, lam) == (3.0, 5, 9.0)
+    assert b.tolist() == [False, True, True, True, False, False, False, True, True, False]
+    # against a library partial sort on random data
+    rs = np.random.default_rng(4)
+    x = rs.standard_normal(5000).astype(np.float32)
+    for k in (1, 5, 64, 4999, 5000):
+        theta, nnz, lam, b = select_k(x, k)
+        want = np.partition(np.abs(x), x.size - k)[x.size - k]
+        assert theta == want and nnz == k and b.sum() == k and lam == np.abs(x).max()
+    # clamps: k above n keeps every non-zero entry, k below 1 keeps the largest
+    assert select_k([1, 0, -2], 10)[1] == 2 and select_k([1, 0, -2], 0)[:2] == (2.0, 1)
+    # same function as the fractional form when the counts agree
+    for s_ppm in (900000, 500000):
+        k = oracle.lib().oracle_topk_count(x.size, s_ppm)
+        assert select_k(x, k)[:3] == select(x, s_ppm)[:3]

@@ -257,11 +257,12 @@ __device__ __forceinline__ void ema_chunk(const TensorDesc& td, int64_t base, fl
   }
 }
 
+template <bool FISHER>
 __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restrict__ tds,
                                                        const ChunkRef* __restrict__ chunks, const LayerDev* layers,
                                                        const GlobalDev* glob, EmaPartial* __restrict__ ema_partials,
                                                        Candidate* cands, uint32_t* counters, StepArg sa,
-                                                       float beta_h, float omb_h, int fisher) {
+                                                       float beta_h, float omb_h) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const ChunkRef cr = chunks[blockIdx.x];
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void k_curv_ema(const TensorDesc* __restr
   ema_chunk<FULL_, SRC_>(td, base, sc.inv_scale, beta_h, omb_h, first, band, list_all, band_lo, band_hi, cr.index, \
                          cr.tensor, cands, counters, above_zeros, maxkey, nonfin)
   const bool full = base + kChunk <= td.numel;
-  if (!fisher) {
+  if constexpr (!FISHER) {
     if (full) TA_EMA(true, -1);
     else TA_EMA(false, -1);
   } else {
@@ -994,8 +995,12 @@ hipError_t launch_grad_stats(const DeviceTables& t, const StepArg& sa, hipStream
 
 hipError_t launch_curv_ema(const DeviceTables& t, const StepArg& sa, float beta_h, float omb_h, int fisher,
                            hipStream_t s) {
-  hipLaunchKernelGGL(k_curv_ema, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                     t.ema_partials, t.cands, t.cand_counters, sa, beta_h, omb_h, fisher);
+  if (fisher)
+    hipLaunchKernelGGL(k_curv_ema<true>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
+                       t.glob, t.ema_partials, t.cands, t.cand_counters, sa, beta_h, omb_h);
+  else
+    hipLaunchKernelGGL(k_curv_ema<false>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
+                       t.glob, t.ema_partials, t.cands, t.cand_counters, sa, beta_h, omb_h);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

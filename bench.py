@@ -26,14 +26,15 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by what the same
 # counters read for the library's plain copy kernel: 2.000 and 1.000; see profiles/).  They belong
 # to the kernel sources with the digest below: when the sources differ, `traffic` is null.
-STEP_SOURCES = ("kernels.hip", "update.hip", "update_body.h", "device_util.h", "numerics.h", "common.h")
-POWER_SOURCES = ("power.hip", "power.h", "numerics.h", "common.h")
+# the files that define the update kernel
+STEP_SOURCES = ("update.hip", "update_body.h", "device_util.h", "numerics.h")
+POWER_SOURCES = ("power.hip", "power.h", "numerics.h")
 MEASURED_TRAFFIC = {
     # k_update<false>, default run of the large_streaming workload
-    "step": {"sources_sha256": "1c268244dbcd5ef79c733f3e2c7907c64ca5a8c46bd6c9c986952b8dfc8538dd", "workload": "large_streaming",
+    "step": {"sources_sha256": "38948805bdac36db298288430170911294a84566ffcac47624e90ec14e5f9726", "workload": "large_streaming",
              "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
     # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
-    "power": {"sources_sha256": "dacb33b548fab17214ea8c0ccb5b6132a89cff0eb91582cabbff05e35fc2dbf1", "workload": "large_streaming",
+    "power": {"sources_sha256": "5cbb185eadd41b14669fb62e658695710a4237dcda5f869e3390ed3ea3047578", "workload": "large_streaming",
               "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.48e9},
               "k_power_gram": {"fetch_bytes": 42.95e9, "write_bytes": 0.01e9}},
 }

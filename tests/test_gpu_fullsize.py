@@ -156,3 +156,87 @@ def test_power_iteration_full_size_sampled_tensors():
         assert np.all(err <= 2 * 2.0 ** -23 * np.abs(want) + 1e-11 * np.max(np.abs(want))), (l, float(err.max()))
         assert abs(info[l].lambda_latched - t.lam_power) <= 2 * 2.0 ** -23 * abs(t.lam_power)
     opt.close()
+
+
+def test_single_tensor_of_maximum_size():
+    """One tensor of 2^31 - 3 elements (the largest the ABI accepts, ragged in every granularity).
+    The per-layer scalars the oracle needs are formed with library reductions on the GPU; the
+    oracle then follows slices at the start, in the middle and at the very end element by element,
+    and the threshold is checked by counting."""
+    import ctypes as C
+
+    dev = torch.device("cuda:0")
+    n = (1 << 31) - 3
+    hyper = dict(get_workload("large_streaming").hyper, tau_curv=1e30)
+    lr, alpha = float(hyper["lr"]), float(hyper["alpha"])
+    g0 = torch.Generator(device=dev)
+    g0.manual_seed(12345)
+    param = torch.randn(n, generator=g0, device=dev, dtype=torch.float32) * 0.1
+    opt = ta.TriAccel(hyper, [param], grad_dtype=FP32)
+    L = oracle.lib()
+    spans = [(0, 1 << 20), (n // 2 - 12345, n // 2 - 12345 + (1 << 20)), (n - (1 << 20) - 1, n)]
+    before = [(to_numpy(param[a:b]).copy(), np.zeros(b - a, np.float32)) for a, b in spans]
+    del param
+    v_prev = None
+    for t in (1, 2):
+        grad = torch.randn(n, generator=g0, device=dev, dtype=torch.float32) * 0.0316
+        z = (torch.randint(0, 2, (n,), generator=g0, device=dev, dtype=torch.int8) * 2 - 1).to(torch.float32)
+        hz = z * 0.37 + torch.randn(n, generator=g0, device=dev, dtype=torch.float32) * 0.19
+        h_prev = opt.curv[0].clone() if t == 2 else None
+        opt.step([grad], [z], [hz], lr=lr, loss_scale=1.0, batch_size=64, mem_used_bytes=8, mem_total_bytes=10)
+        res = opt.result()
+        st = opt.layer_state()[0]
+        assert res.skipped == 0 and st.numel == n
+        # curvature EMA with library element-wise operations (same fp32 operation order, no fma in torch:
+        # the first probe is a product only, the second step is checked on the slices below)
+        u = z * hz
+        if t == 1:
+            assert torch.equal(opt.curv[0], u)
+        lam = float(opt.curv[0].abs().max().item())
+        assert st.lambda_ == lam
+        k = n - (n * int(hyper["sparsity_ppm"])) // 1000000
+        check_properties(opt, 0, st, k)
+        # statistics with library reductions in fp64, by parts to bound the temporary memory
+        parts = torch.split(grad, 1 << 28)
+        mean = sum(float(p.double().sum().item()) for p in parts) / n
+        var = sum(float(((p.double() - mean) ** 2).sum().item()) for p in parts) / n
+        assert abs(st.mean - mean) <= 1e-5 * max(abs(mean), var ** 0.5) and abs(st.var - var) <= 1e-5 * var
+        v = np.float32(var) if v_prev is None else np.float32(L.oracle_var_ema(v_prev, var, np.float32(hyper["beta_var"]), 0))
+        assert abs(st.v - float(v)) <= 1e-5 * float(v)
+        for tau in (hyper["tau_low"], hyper["tau_high"]):
+            assert abs(float(v) - tau) / tau > 1e-3
+        v_prev = v
+        code = int(L.oracle_precision_code(v, np.float32(lam), np.float32(hyper["tau_low"]), np.float32(hyper["tau_high"]),
+                                           np.float32(hyper["tau_curv"])))
+        eta = np.float32(L.oracle_eta(np.float32(lr), np.float32(alpha), np.float32(lam)))
+        assert st.code == code and np.float32(st.eta) == eta
+        # the oracle on the slices: update (and, at the second step, the EMA recurrence)
+        prev_code = FP32 if t == 1 else prev_code_last
+        for (a, b), (pbuf, mbuf) in zip(spans, before):
+            m = b - a
+            raw = np.zeros(4 * m, np.uint8)
+            raw.view(pbuf.dtype)[:m] = pbuf
+            gs = to_numpy(grad[a:b])
+            L.oracle_update(raw.ctypes.data, prev_code, code, gs.ctypes.data, FP32, mbuf.ctypes.data, m, np.float32(1.0),
+                            np.float32(hyper["weight_decay"]), np.float32(hyper["momentum"]), eta)
+            view = raw.view(np.float32 if code == FP32 else np.uint16)[:m]
+            got = to_numpy(opt.param(0, code)[a:b])
+            assert np.array_equal(got.view(view.dtype), view), (t, a)
+            assert np.array_equal(to_numpy(opt.mom[0][a:b]).view(np.uint32), mbuf.view(np.uint32)), (t, a)
+            if t == 2:
+                hs = to_numpy(h_prev[a:b]).copy()
+                zs, hzs = to_numpy(z[a:b]), to_numpy(hz[a:b])   # held until the call returns
+                flag = C.c_uint32(0)
+                L.oracle_curv_ema(zs.ctypes.data, hzs.ctypes.data, hs.ctypes.data, m,
+                                  np.float32(1.0), np.float32(hyper["beta_curv"]), 0, C.byref(flag))
+                assert np.array_equal(to_numpy(opt.curv[0][a:b]).view(np.uint32), hs.view(np.uint32)), a
+        before = [(view_of(opt, 0, code, a, b), mb) for (a, b), (_, mb) in zip(spans, before)]
+        prev_code_last = code
+        print(f"maximum-size tensor: step {t} ok (code {code}, theta {st.theta}, nnz {st.nnz})", flush=True)
+        del grad, z, hz, u, parts
+    opt.close()
+
+
+def view_of(opt, l, code, a, b):
+    """Stored parameters of a slice in their stored dtype (numpy, bit-preserving)."""
+    return to_numpy(opt.param(l, code)[a:b]).copy()

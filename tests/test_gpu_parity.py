@@ -6,6 +6,7 @@ import torch
 from workloads import get_workload
 from workloads.configs import BF16, FP16, FP32, Workload, _DEFAULT_HYPER
 from _gpu_harness import Pair
+from _runner import to_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -327,3 +328,58 @@ def test_fixed_top_k_instead_of_a_fraction():
         p = Pair(wl).run(8)
         assert [t.nnz for t in p.orc.tensors] == [min(k, n) for n in sizes]
         p.close()
+
+
+def test_every_outcome_of_the_band_check_is_reached_with_parity():
+    """Drives three tensors through curvature streams that make the threshold selection take each of
+    its paths (diagnostic code of the layer record): 0 all keys listed (small tensor), 1 predicted
+    band held, 2 no band, 3 threshold above the band, 4 below it, 5 too many keys in the band,
+    6 fewer non-zero magnitudes than k.  Every step is compared with the oracle."""
+    sizes = [300007, 5000, 70001]
+    wl = custom(sizes, name="large_streaming", steps=150, tau_curv=1e30)
+    p = Pair(wl)
+    n = len(sizes)
+    seen = [set() for _ in range(n)]
+    rs = np.random.default_rng(3)
+
+    def run(t, hz_of=None):
+        g, z, hz = p.inputs(t)
+        if hz_of is not None:
+            hz = [hz_of(l, z[l], hz[l]) for l in range(n)]
+        p.step(g, z, hz, label=f"t={t}")
+        for l, s in enumerate(p.gpu.layer_state()):
+            seen[l].add(int(s.sel_outcome))
+
+    def sparse_first(l, z, hz):
+        if l != 2:
+            return hz
+        keep = torch.from_numpy(rs.uniform(size=z.numel()) < 0.01)
+        return torch.where(keep, hz, torch.zeros_like(hz))
+
+    t = 1
+    run(t, sparse_first)                      # tensor 2: fewer non-zero magnitudes than k
+    for t in range(2, 46):                    # settle: the band switches on and holds
+        run(t)
+    assert 6 in seen[2] and 0 in seen[1] and 2 in seen[0] and 1 in seen[0], seen
+    run(46, lambda l, z, hz: hz * 40.0)       # curvature jumps up: threshold above the band
+    for t in range(47, 90):
+        run(t)
+    run(90, lambda l, z, hz: hz * 0.0)        # a zero sample: every magnitude shrinks by beta_h at once
+    for t in range(91, 130):
+        run(t)
+
+    def collapse(l, z, hz):
+        # choose the sample so that the new h is (almost) one value, the last threshold, everywhere:
+        # all keys land inside the predicted band, more than the lists can take
+        o = p.orc.tensors[l]
+        if l != 0:
+            return hz
+        target = np.float32(o.theta)
+        u = (target - np.float32(0.9) * o.curv) / np.float32(0.1)
+        return torch.from_numpy((u * to_numpy(z)).astype(np.float32))
+
+    run(130, collapse)
+    for t in range(131, 136):
+        run(t)
+    assert {1, 2, 3, 4, 5} <= seen[0], seen
+    p.close()

@@ -104,6 +104,10 @@ def main():
     ap.add_argument("--switch-stress", action="store_true",
                     help="variance EMA off and a gradient scale cycling over three decades: every layer changes "
                          "its storage precision at every step (all updates go through the in-place resize)")
+    ap.add_argument("--settle", type=int, default=64,
+                    help="the optimizer state is first brought to at least this many steps into the run (untimed, "
+                         "before the warm-up steps): the exact threshold needs no second pass over the curvature "
+                         "once its prediction has converged, about 40 steps in; 0 measures the first steps of a run")
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,8 +124,8 @@ def main():
         print("bench.py: the library runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(a sharded job would run one such step per rank on its own tensors)", file=sys.stderr)
         sys.exit(2)
-    if args.steps < 1 or args.steps > 63:
-        print("bench.py: --steps must be in 1..63 (stage timings are kept for the last 64 steps)", file=sys.stderr)
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -157,7 +161,7 @@ def main():
     stream = torch.cuda.Stream(device=dev) if (args.graph or args.own_stream) else None
     opt = ta.TriAccel(hyper, params, grad_dtype=wl.grad_dtype, stream=stream)
     del params
-    R = max(1, min(args.input_sets, K + W))
+    R = max(1, min(args.input_sets, K + max(W, args.settle)))
     sets = []
     # generator steps to draw the input batches from (steps with injected inf/NaN are left out:
     # a skipped step does no work and would flatter the average)
@@ -200,35 +204,38 @@ def main():
         opt.step(g, z, hz, lr=lr, loss_scale=scale, batch_size=int(hyper["batch_size"]),
                  mem_used_bytes=8, mem_total_bytes=10)
 
-    for i in range(W):
+    # bring the run to its steady state first when the warm-up alone is shorter than that takes
+    P = max(0, args.settle - W)
+    for i in range(P):
+        one(i)
+    for i in range(P, P + W):
         one(i)
     res = opt.result()
     assert not res.skipped
     codes_before = [s.code for s in opt.layer_state()]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(W, W + K):
+    for i in range(P + W, P + W + K):
         one(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
     res = opt.result()
-    assert not res.skipped and res.step_index == W + K
-    upd_ms_timed = None if args.graph else sum(opt.stage_times(back)[4] for back in range(K)) / K
-    resize_ms_timed = sum(opt.stage_times(back)[5] for back in range(K)) / K if args.switch_stress and not args.graph else None
+    assert not res.skipped and res.step_index == P + W + K
+    KP = min(K, 63)  # the library keeps the event times of the last 64 steps
+    upd_ms_timed = None if args.graph else sum(opt.stage_times(back)[4] for back in range(KP)) / KP
+    resize_ms_timed = sum(opt.stage_times(back)[5] for back in range(KP)) / KP if args.switch_stress and not args.graph else None
     # stage breakdown: the same number of steps again, launched kernel by kernel with an event at
     # every stage boundary (not part of the timed region)
     opt.set_profiling(1)
-    for i in range(W + K, W + 2 * K):
+    for i in range(P + W + K, P + W + K + KP):
         one(i)
     opt.result()
     state = opt.layer_state()
     codes = [s.code for s in state]
     prev_codes = [s.prev_code for s in state]
-    stage_ms = [[0.0] * len(ta.STAGE_NAMES) for _ in range(K)]
-    for back in range(K):
-        stage_ms[K - 1 - back] = opt.stage_times(back)
-    mean_ms = {name: sum(s[i] for s in stage_ms) / K for i, name in enumerate(ta.STAGE_NAMES)}
+    stage_ms = [opt.stage_times(back) for back in range(KP)]
+    mean_ms = {name: sum(s[i] for s in stage_ms) / KP for i, name in enumerate(ta.STAGE_NAMES)}
 
     # algorithmic traffic of the last timed step (codes are stationary over the timed region
     # unless a layer switched; the count of switches is reported)
@@ -253,9 +260,6 @@ def main():
     if args.switch_stress:
         # every step of the cycle sends all tensors through one of the two kernels; report the in-place
         # resize with its bytes and time averaged over the steps of the timed region
-        per_step = []
-        for back in range(K):
-            per_step.append(opt.stage_times(back))
         dominant = "k_update_resize (in-place update while the storage size changes; all its launches of a step)"
         upd_ms = mean_ms["update_resize"] if resize_ms_timed is None else resize_ms_timed
         # two of the three steps of the cycle change the size: 2 -> 4 bytes and 4 -> 2 bytes per parameter
@@ -286,6 +290,7 @@ def main():
             "layers_switched_in_timed_region": switched,
             "tensors_needing_extra_passes_over_h_last_step": sum(1 for x in sel_passes if x),
             "input_sets": R,
+            "settle_steps_before_warmup": P,
             "launch": "HIP graph replay" if args.graph else "kernel by kernel",
             "switch_stress": bool(args.switch_stress),
         },

@@ -55,8 +55,10 @@ __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __
     if (phase > last_phase) continue;
     const uint32_t c_lo = 1u << (phase - 1u);  // phase > kSerialPhase >= 1
     const uint32_t c_hi = min(1u << phase, td.n_chunks);
+    // a chunk c >= 1 reads and writes disjoint bytes (its element range at the old and at the new
+    // size do not meet), so these phases need no synchronisation between its loads and its stores
     for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
-      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
+      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, false);
   }
 }
 

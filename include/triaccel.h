@@ -19,7 +19,11 @@
  * library owns only its internal workspace, released by triaccel_destroy().
  *
  * Every device operation is enqueued on the HIP stream given to triaccel_init();
- * triaccel_step() never synchronises.  One step may be in flight per handle.
+ * triaccel_step() never synchronises; steps may be enqueued back to back, and
+ * triaccel_result() reports the last one.
+ * A handle belongs to the device that was current when it was created; calls that
+ * enqueue work must be made with that device current (TRIACCEL_E_HIP otherwise).
+ * Calls on one handle must not overlap in time; different handles are independent.
  *
  * Precision codes / dtypes:  0 = FP16 (IEEE binary16), 1 = BF16, 2 = FP32 --
  * the order of the cases in the precision rule, so "promotion" is +1.

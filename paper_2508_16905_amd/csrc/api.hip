@@ -245,6 +245,17 @@ int replay_step(triaccel_ctx* h, const StepScalars& sc, bool any_probe) {
   return TRIACCEL_OK;
 }
 
+// Kernels are launched on the current device: it must be the one the handle was created on.
+int check_device(const triaccel_ctx* h) {
+  int dev = -1;
+  TA_HIP(hipGetDevice(&dev));
+  if (dev != h->device) {
+    g_last_error = "the current HIP device is not the one the handle was created on";
+    return TRIACCEL_E_HIP;
+  }
+  return TRIACCEL_OK;
+}
+
 int32_t batch_rule(const triaccel_config& cfg, int32_t batch, uint64_t used, uint64_t total) {
   // Sec. 3.3: strict comparisons as printed, then the clamp.
   const double u = (double)used, m = (double)total;
@@ -414,6 +425,7 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
   if (!(args->loss_scale > 0.0f) || !std::isfinite(args->loss_scale) || !std::isfinite(args->lr))
     return TRIACCEL_E_INVALID_ARG;
+  if (int drc = check_device(h)) return drc;
   const bool need_mom = h->cfg.momentum != 0.0f;
   const bool fisher = h->cfg.curvature_source == 1;
   bool any_probe = false;
@@ -609,6 +621,7 @@ int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor* vectors,
   if (!vectors) return TRIACCEL_E_NULL_PTR;
   if ((uint32_t)n != h->n) return TRIACCEL_E_SHAPE_MISMATCH;
   if (k < 1 || k > h->cfg.power_k) return TRIACCEL_E_INVALID_ARG;
+  if (int drc = check_device(h)) return drc;
   for (int32_t i = 0; i < n; ++i) {
     const triaccel_power_tensor& v = vectors[i];
     if (!v.u || !v.hu) return TRIACCEL_E_NULL_PTR;

@@ -121,7 +121,7 @@ struct LayerDev {
   uint32_t count_above;    // the next histogram pass must count the keys above its window
   uint32_t hist_arrived;   // chunks whose keys are in this round's histogram (cleared by the scan)
   // accumulators filled by atomics during a step and cleared by the kernel that consumes them
-  uint32_t acc_above, acc_zeros, acc_maxkey, acc_nonfinite;
+  uint32_t acc_above, acc_maxkey, acc_nonfinite;
 };
 
 // Small global record (device), copied to pinned host memory at the end of a step.

@@ -885,7 +885,6 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   ls.dens_count = 0;
   ls.dens_width = 0;
   ls.acc_above = 0;
-  ls.acc_zeros = 0;
 }
 
 // ---------------------------------------------------------------------------------------------

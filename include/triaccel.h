@@ -139,7 +139,8 @@ typedef struct {
   float v;              /* variance EMA v_l (Sec. 3.1)                                              */
   float theta;          /* magnitude threshold of the mask                                          */
   uint32_t nnz;         /* popcount of the mask                                                     */
-  float lambda;         /* largest kept |h_i|                                                       */
+  float lambda;         /* lambda_l: largest kept |h_i|, or with lambda_source == 1 the latched
+                           power-iteration value                                                    */
   float lambda_ctrl;    /* lambda latched at the last control step (used by eta and promotion)      */
   float eta;            /* per-layer step size (Sec. 3.2)                                           */
   int32_t code;         /* precision the parameters are stored in now                               */

@@ -192,3 +192,13 @@ def test_state_round_trip_resumes_bit_identically():
     assert lib.triaccel_set_state(c.handle, blob, len(blob)) == -1     # other hyper-parameters
     for o in (a, b, other, c):
         o.close()
+
+
+def test_example_training_loop_reduces_the_loss():
+    # the caller's side of the contract (autograd, loss scaling, Hessian-vector products, reading the
+    # parameters back in the stored precision) around the library: the fit must improve markedly
+    from paper_2508_16905_amd.examples.train_mlp import train
+
+    losses = train(steps=150, verbose=False)
+    first, last = sum(losses[:5]) / 5, sum(losses[-10:]) / 10
+    assert last < 0.35 * first, (first, last)

@@ -268,7 +268,7 @@ def main():
     step_gbps = total_bytes / 1e9 / (ms_per_step / 1e3)
 
     out = {
-        "metric": "fused Tri-Accel step throughput (params/s; achieved HBM GB/s in roofline)",
+        "metric": "fused Tri-Accel step params/sec and achieved HBM GB/s (% of peak), 1 GPU",
         "value": N / (ms_per_step / 1e3),
         "unit": "params/s",
         "n_gpus": 1,

@@ -202,3 +202,25 @@ def test_example_training_loop_reduces_the_loss():
     losses = train(steps=150, verbose=False)
     first, last = sum(losses[:5]) / 5, sum(losses[-10:]) / 10
     assert last < 0.35 * first, (first, last)
+
+
+def test_create_and_destroy_release_the_workspace():
+    wl = get_workload("resnet18")
+    params = [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)]
+    g, z, hz = inputs(wl, 1)
+
+    def cycle(hyper):
+        opt = ta.TriAccel(hyper, params, grad_dtype=wl.grad_dtype)
+        opt.step(g, z, hz)
+        opt.result()
+        opt.close()
+
+    cycle(wl.hyper)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for i in range(40):
+        cycle(dict(wl.hyper, power_k=5) if i % 2 else wl.hyper)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    # the wrapper's own tensors return to PyTorch's cache; the library's hipMalloc'ed workspace must come back
+    assert free0 - free1 < 64 * 2**20, (free0, free1)

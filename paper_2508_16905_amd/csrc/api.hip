@@ -177,9 +177,8 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
   TA_HIP(launch_layer(T, sa, h->hp, s));
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[3], s));
   if (any_probe) {
-    // fallback radix select: a predicted window that misses, then 11 + 11 + 9 key bits, is the
-    // most it can take; every launch leaves at once when no tensor is (still) in histogram mode
-    for (int round = 0; round < 4; ++round) TA_HIP(launch_hist_pass(T, sa, s));
+    // fallback radix select; leaves at once when no tensor is in histogram mode
+    TA_HIP(launch_hist_pass(T, sa, s));
   }
   const bool elem = h->cfg.elementwise_scale == 1;
   if (elem && any_probe) {

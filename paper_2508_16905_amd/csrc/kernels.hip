@@ -537,20 +537,26 @@ __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, Glo
 
 // ---------------------------------------------------------------------------------------------
 // Scan after a histogram pass, by one workgroup for one tensor in mode kSelHist: read the
-// tensor's histogram, clear it, and decide whether theta is now exact, lies in a range whose keys
-// can be listed by the mask pass, or needs a finer histogram.  Uniform over the workgroup.
+// tensor's histogram (from memory, clearing it, or already complete in LDS), and decide whether
+// theta is now exact, lies in a range whose keys can be listed by the mask pass, or needs a finer
+// histogram.  Uniform over the workgroup.
 // ---------------------------------------------------------------------------------------------
 __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob, uint32_t* hist,
-                            uint32_t step_id, uint32_t* s_hist, uint32_t* s_part, uint32_t* s_out) {
+                            uint32_t step_id, uint32_t* s_hist, uint32_t* s_part, uint32_t* s_out, bool from_global) {
   const uint32_t bins = ls.win_bins, lo = ls.win_lo, shift = ls.win_shift;
   uint32_t* gh = hist + (size_t)l * kHistBins;
   uint32_t local = 0;
   for (uint32_t b = threadIdx.x; b < kHistBins; b += kThreads) {
-    // counted by other workgroups of the running kernel: read at device scope
-    const uint32_t v = (b < bins) ? __hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-    s_hist[b] = v;
+    uint32_t v;
+    if (from_global) {
+      // counted by other workgroups of the running kernel: read at device scope
+      v = (b < bins) ? __hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      s_hist[b] = v;
+      if (v) gh[b] = 0;
+    } else {
+      v = (b < bins) ? s_hist[b] : 0u;
+    }
     local += v;
-    if (v) gh[b] = 0;
   }
   local = wave_sum(local);
   if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = local;
@@ -603,12 +609,16 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
 }
 
 // ---------------------------------------------------------------------------------------------
-// One fallback round: histogram pass over the tensors in histogram mode, each workgroup over its
-// share of the chunk list.  The workgroup that is the last to deliver its part of a tensor's
-// histogram also scans it (select_scan), so a round is one launch and no workgroup ever waits
-// for another.  Leaves at once when no tensor is in histogram mode: a workgroup that sees the
-// pending count at zero owns no chunk of a tensor still being counted, because a tensor's scan,
-// which alone lowers the count, needs every workgroup owning one of its chunks to have arrived.
+// Fallback radix select: histogram pass over the tensors in histogram mode, each workgroup over
+// its share of the chunk list.  The workgroup that is the last to deliver its part of a tensor's
+// histogram also scans it (select_scan), so no workgroup ever waits for another.  One round is
+// what a tensor normally needs; if the scan still cannot confine the threshold (a predicted
+// window that missed, more keys in the pivot bin than can be listed: at most three more rounds,
+// 11 + 11 + 9 key bits), the same workgroup makes the further passes over the whole tensor on
+// its own -- slow for a large tensor, but rare, and it keeps the fallback to one launch.
+// Leaves at once when no tensor is in histogram mode: a workgroup that sees the pending count at
+// zero owns no chunk of a tensor still being counted, because a tensor's scan, which alone
+// lowers the count, needs every workgroup owning one of its chunks to have arrived.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
                                                         const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
@@ -652,7 +662,22 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
         __syncthreads();
         if (s_last) {
           __threadfence();  // acquire: the scan below reads what the other workgroups added
-          select_scan((uint32_t)cur, td, layers[cur], glob, hist, sc.step_id, s_hist, s_part, s_out);
+          select_scan((uint32_t)cur, td, layers[cur], glob, hist, sc.step_id, s_hist, s_part, s_out, true);
+          for (int extra = 0; extra < 3; ++extra) {
+            if (layers[cur].mode != kSelHist) break;  // written before the barrier that ends the scan
+            for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+            __syncthreads();
+            // after a scan the number of keys above the window is known
+            const Window w2{layers[cur].win_lo, layers[cur].win_shift, layers[cur].win_bins};
+            uint32_t unused = 0;
+            for (uint32_t q = 0; q < td.n_chunks; ++q) {
+              const int64_t b2 = (int64_t)q * kChunk;
+              if (b2 + kChunk <= td.numel) hist_chunk<true>(td, b2, w2, s_hist, false, unused);
+              else hist_chunk<false>(td, b2, w2, s_hist, false, unused);
+            }
+            __syncthreads();
+            select_scan((uint32_t)cur, td, layers[cur], glob, hist, sc.step_id, s_hist, s_part, s_out, false);
+          }
           for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
           __syncthreads();
         }

@@ -24,8 +24,7 @@ struct StepSize {
 
 template <int GD, int PD, int ND, bool FULL, bool MOM, bool ELEM>
 __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base, float inv_scale, float wd, float mu,
-                                             const StepSize& ss, bool barrier) {
-  const int tid = threadIdx.x;
+                                             const StepSize& ss, bool barrier, int tid) {
   float g[kRows][4], th[kRows][4], m[kRows][4], h[ELEM ? kRows : 1][4];
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
@@ -76,36 +75,36 @@ __device__ __forceinline__ void update_chunk(const TensorDesc& td, int64_t base,
 
 template <bool ELEM, int GD, int PD, int ND>
 __device__ __forceinline__ void update_dispatch2(const TensorDesc& td, int64_t base, float inv_scale, float wd,
-                                                 float mu, const StepSize& ss, bool barrier) {
+                                                 float mu, const StepSize& ss, bool barrier, int tid) {
   const bool full = base + kChunk <= td.numel;
   const bool mom = td.mom != nullptr;
   if (full) {
-    if (mom) update_chunk<GD, PD, ND, true, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-    else update_chunk<GD, PD, ND, true, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
+    if (mom) update_chunk<GD, PD, ND, true, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier, tid);
+    else update_chunk<GD, PD, ND, true, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier, tid);
   } else {
-    if (mom) update_chunk<GD, PD, ND, false, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
-    else update_chunk<GD, PD, ND, false, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier);
+    if (mom) update_chunk<GD, PD, ND, false, true, ELEM>(td, base, inv_scale, wd, mu, ss, barrier, tid);
+    else update_chunk<GD, PD, ND, false, false, ELEM>(td, base, inv_scale, wd, mu, ss, barrier, tid);
   }
 }
 
 template <bool ELEM, int GD, int PD>
 __device__ __forceinline__ void update_dispatch1(int nd, const TensorDesc& td, int64_t base, float inv_scale,
-                                                 float wd, float mu, const StepSize& ss, bool barrier) {
+                                                 float wd, float mu, const StepSize& ss, bool barrier, int tid) {
   switch (nd) {
-    case kFP32: update_dispatch2<ELEM, GD, PD, kFP32>(td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch2<ELEM, GD, PD, kBF16>(td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch2<ELEM, GD, PD, kFP16>(td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kFP32: update_dispatch2<ELEM, GD, PD, kFP32>(td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    case kBF16: update_dispatch2<ELEM, GD, PD, kBF16>(td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    default: update_dispatch2<ELEM, GD, PD, kFP16>(td, base, inv_scale, wd, mu, ss, barrier, tid); break;
   }
 }
 
 template <bool ELEM, int GD>
 __device__ __forceinline__ void update_dispatch0(int pd, int nd, const TensorDesc& td, int64_t base,
                                                  float inv_scale, float wd, float mu, const StepSize& ss,
-                                                 bool barrier) {
+                                                 bool barrier, int tid) {
   switch (pd) {
-    case kFP32: update_dispatch1<ELEM, GD, kFP32>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch1<ELEM, GD, kBF16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch1<ELEM, GD, kFP16>(nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kFP32: update_dispatch1<ELEM, GD, kFP32>(nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    case kBF16: update_dispatch1<ELEM, GD, kBF16>(nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    default: update_dispatch1<ELEM, GD, kFP16>(nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
   }
 }
 
@@ -113,11 +112,11 @@ __device__ __forceinline__ void update_dispatch0(int pd, int nd, const TensorDes
 // specialised for the combination.
 template <bool ELEM>
 __device__ __forceinline__ void update_any(const TensorDesc& td, int pd, int nd, int64_t base, float inv_scale,
-                                           float wd, float mu, const StepSize& ss, bool barrier) {
+                                           float wd, float mu, const StepSize& ss, bool barrier, int tid) {
   switch (td.grad_dtype) {
-    case kFP32: update_dispatch0<ELEM, kFP32>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    case kBF16: update_dispatch0<ELEM, kBF16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
-    default: update_dispatch0<ELEM, kFP16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier); break;
+    case kFP32: update_dispatch0<ELEM, kFP32>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    case kBF16: update_dispatch0<ELEM, kBF16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
+    default: update_dispatch0<ELEM, kFP16>(pd, nd, td, base, inv_scale, wd, mu, ss, barrier, tid); break;
   }
 }
 

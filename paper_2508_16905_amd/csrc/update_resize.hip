@@ -12,26 +12,32 @@ namespace triaccel {
 // in descending order for the same reason.
 //
 // The phases up to kSerialPhase (the first kSerialChunks chunks) are done by ONE workgroup per
-// tensor, chunk after chunk in the same order (ascending when narrowing, descending when
-// widening; every chunk loads, synchronises, then stores), in a single launch; each later phase
-// is a launch of its own.  With L = the last phase of the largest tensor there are
+// tensor in a single launch: a workgroup of 1024 threads takes four consecutive chunks per
+// iteration (every 256-thread part loads its chunk, the workgroup synchronises, then stores), in
+// ascending order when narrowing and in descending order when widening; what such a group of four
+// overwrites was read by an earlier iteration, or by the same one before its barrier.  Each later
+// phase is a launch of its own.  With L = the last phase of the largest tensor there are
 // n_launch = 1 + max(0, L - kSerialPhase) launches:
 //   narrowing:  launch 0 = serial part, launch j >= 1 = phase kSerialPhase + j;
 //   widening:   launch j < n_launch - 1 = phase L - j, launch n_launch - 1 = serial part.
-// A tensor with fewer phases than the largest one skips the launches beyond its own.
-constexpr uint32_t kSerialPhase = 6;
-constexpr uint32_t kSerialChunks = 1u << kSerialPhase;  // 64 chunks = 262,144 elements
+// A tensor with fewer phases than the largest one skips the launches beyond its own.  The first
+// and the last launch run with 1024 threads per workgroup (their phase work is then spread over
+// the four parts of a workgroup), the others with 256.
+constexpr uint32_t kSerialPhase = 8;
+constexpr uint32_t kSerialChunks = 1u << kSerialPhase;  // 256 chunks = 1,048,576 elements
+constexpr int kSerialParts = 4;                          // 256-thread parts of the serial workgroup
 
 template <bool ELEM>
-__global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds,
-                                                            const LayerDev* layers, const GlobalDev* glob,
-                                                            const uint32_t* trans_list, uint32_t n_tensors,
-                                                            uint32_t launch, uint32_t n_launch, StepArg sa, float wd,
-                                                            float mu, float alpha) {
+__global__ __launch_bounds__(kSerialParts * kThreads) void k_update_resize(
+    const TensorDesc* __restrict__ tds, const LayerDev* layers, const GlobalDev* glob, const uint32_t* trans_list,
+    uint32_t n_tensors, uint32_t launch, uint32_t n_launch, StepArg sa, float wd, float mu, float alpha) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t count = glob->trans_count[sc.step_id & 1u];
   const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
+  const uint32_t parts = blockDim.x / kThreads;  // 1 or kSerialParts
+  const uint32_t part = threadIdx.x / kThreads;
+  const int lane = (int)(threadIdx.x % kThreads);
   for (uint32_t i = 0; i < count; ++i) {
     const uint32_t l = list[i];
     const TensorDesc td = tds[l];
@@ -43,9 +49,12 @@ __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __
     if (serial) {
       if (i % gridDim.x != blockIdx.x) continue;  // one workgroup per tensor
       const uint32_t n_ser = min(kSerialChunks, td.n_chunks);
-      for (uint32_t q = 0; q < n_ser; ++q) {
-        const uint32_t c = narrowing ? q : n_ser - 1u - q;
-        update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true);
+      const uint32_t n_it = (n_ser + parts - 1u) / parts;
+      for (uint32_t it = 0; it < n_it; ++it) {
+        const uint32_t c = (narrowing ? it : n_it - 1u - it) * parts + part;
+        // every thread of the workgroup meets exactly one barrier per iteration
+        if (c < n_ser) update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true, lane);
+        else __syncthreads();
       }
       continue;
     }
@@ -57,8 +66,8 @@ __global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __
     const uint32_t c_hi = min(1u << phase, td.n_chunks);
     // a chunk c >= 1 reads and writes disjoint bytes (its element range at the old and at the new
     // size do not meet), so these phases need no synchronisation between its loads and its stores
-    for (uint32_t c = c_lo + blockIdx.x; c < c_hi; c += gridDim.x)
-      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, false);
+    for (uint32_t c = c_lo + blockIdx.x * parts + part; c < c_hi; c += gridDim.x * parts)
+      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, false, lane);
   }
 }
 
@@ -85,11 +94,13 @@ hipError_t launch_update_resize(const DeviceTables& t, const StepArg& sa, float 
   if (grid < 1) grid = 1;
   if (grid > t.persistent_grid) grid = t.persistent_grid;
   for (uint32_t launch = 0; launch < n_launch; ++launch) {
+    // the launches that hold a serial part use the wide workgroup
+    const uint32_t threads = (launch == 0 || launch == n_launch - 1u) ? kSerialParts * kThreads : kThreads;
     if (elem)
-      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(threads), 0, s, t.tensors, t.layers, t.glob,
                          t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
     else
-      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(threads), 0, s, t.tensors, t.layers, t.glob,
                          t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
     TA_LAUNCH_CHECK();
   }

@@ -177,8 +177,11 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
   TA_HIP(launch_layer(T, sa, h->hp, s));
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[3], s));
   if (any_probe) {
-    // fallback radix select; leaves at once when no tensor is in histogram mode
-    TA_HIP(launch_hist_pass(T, sa, s));
+    // fallback radix select: two rounds at full width (a first window, then a refinement or the
+    // other side of a window that missed); rarer further rounds are made inside the second launch.
+    // Each launch leaves at once when no tensor is (still) in histogram mode.
+    TA_HIP(launch_hist_pass(T, sa, 0, s));
+    TA_HIP(launch_hist_pass(T, sa, 8, s));
   }
   const bool elem = h->cfg.elementwise_scale == 1;
   if (elem && any_probe) {
@@ -343,6 +346,7 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
     ls.win_lo = 0;
     ls.win_shift = kFullShift;
     ls.win_bins = kHistBins;
+    ls.win_hi = 0x80000000u;
     ls.var_ext = 3.0e38f;  // no extrapolation error measured yet
   }
   DeviceTables& T = c->t;

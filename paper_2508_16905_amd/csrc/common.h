@@ -19,6 +19,8 @@ constexpr int kFinishThreads = 1024;          // workgroup of the per-tensor thr
 constexpr int kHistBins = 2048;
 constexpr int kHistBits = 11;
 constexpr uint32_t kFullShift = 20;          // 2048 bins of 2^20 keys cover all 2^31 keys
+constexpr uint32_t kFirstShift = 13;         // first window without a prediction: 2048 bins of 2^13 keys = the two
+                                             // octaves below the largest key
 constexpr uint32_t kMinPredShift = 6;        // finest predicted window: 2048 bins of 64 keys
 constexpr uint32_t kUnknownPredErr = 1u << 16;  // assumed prediction error (keys) before any is measured
 constexpr uint32_t kCandCap = 262144;        // keys a tensor may list in total (entries)
@@ -110,6 +112,7 @@ struct LayerDev {
   uint32_t window_missed;  // the predicted window did not contain theta this step
   uint32_t mode;           // SelMode
   uint32_t win_lo, win_shift, win_bins;  // histogram window (fallback passes): bin = (key - win_lo) >> win_shift
+  uint32_t win_hi;         // keys in [win_lo, win_hi) are counted; win_hi <= win_lo + (win_bins << win_shift)
   uint32_t predicted;      // the window was centred on the previous theta
   uint32_t passes;         // scans done in this step (0 = the first histogram has not been scanned yet)
   uint32_t k_rem;          // rank still to resolve inside [rng_lo, rng_hi) (1 = largest)

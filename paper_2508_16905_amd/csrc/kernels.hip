@@ -149,6 +149,7 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
 // ---------------------------------------------------------------------------------------------
 struct Window {
   uint32_t lo, shift, bins;
+  uint32_t hi;  // keys in [lo, hi) are counted; hi <= lo + (bins << shift)
 };
 
 // Flush a workgroup's LDS histogram to the tensor's global one and clear it.
@@ -345,8 +346,7 @@ __device__ __forceinline__ void hist_chunk(const TensorDesc& td, int64_t base, c
     for (int i = 0; i < 4; ++i) {
       const uint32_t key = f2u(h[r][i]) & 0x7fffffffu;  // guarded fill 0 is never counted
       if (key != 0u && key >= w.lo) {
-        const uint32_t bin = (key - w.lo) >> w.shift;
-        if (bin < w.bins) atomicAdd(&s_hist[bin], 1u);
+        if (key < w.hi) atomicAdd(&s_hist[(key - w.lo) >> w.shift], 1u);
         else if (count_above) ++above;
       }
     }
@@ -519,14 +519,19 @@ __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, Glo
       ls.above = nonzero;
       ls.sel_count = 0;
     } else {
-      // histogram over the predicted window if there is one, else over the full key range
+      // histogram over the predicted window if there is one; else over the kFirstOctaves octaves
+      // below the largest key, where the threshold of a top-k selection normally lies (nothing is
+      // above that window, so the count above it is known)
       ls.mode = kSelHist;
       ls.mask_done = 0;
       ls.above = 0;
       ls.count_above = ls.predicted;
       if (!ls.predicted) {
-        ls.win_lo = 0;
-        ls.win_shift = kFullShift;
+        const uint32_t span = (uint32_t)kHistBins << kFirstShift;
+        const uint32_t hi = maxkey + 1u;
+        ls.win_lo = hi > span ? hi - span : 0u;
+        ls.win_hi = hi;
+        ls.win_shift = kFirstShift;
         ls.win_bins = kHistBins;
       }
       atomicAdd(&glob->hist_pending[step_id & 1u], 1u);
@@ -576,14 +581,31 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
     ls.hist_arrived = 0;
     ls.passes = ls.passes + 1;
     if (missed) {
-      // the window (a predicted one) does not contain theta: restart with the full key range
-      ls.win_lo = 0;
-      ls.win_shift = kFullShift;
+      // The window does not contain theta.  Continue with what lies on the side where it must be:
+      // between the window and the largest key (nothing is above that), or below the window (then
+      // every key counted so far is above the new window).
+      const uint32_t old_hi = ls.win_hi;
+      uint32_t new_lo, new_hi;
+      if (above >= k) {
+        new_lo = old_hi;
+        new_hi = ls.acc_maxkey + 1u;  // acc_maxkey >= old_hi: some key lies above the window
+        ls.above = 0;
+      } else {
+        new_lo = 0;
+        new_hi = lo;
+        ls.above = above + in_window;
+      }
+      uint32_t ns = 0;
+      while (ns < kFullShift && ((uint32_t)kHistBins << ns) < new_hi - new_lo) ++ns;
+      ls.win_lo = new_lo;
+      ls.win_hi = new_hi;
+      ls.win_shift = ns;
       ls.win_bins = kHistBins;
-      ls.above = 0;
       ls.window_missed = 1;
     } else {
       const uint32_t new_lo = lo + (hit.bin << shift);
+      // the bin ends where the window ends (its last bin may be cut short)
+      const uint32_t new_hi = min(new_lo + (1u << shift), ls.win_hi);
       ls.above = above + hit.higher;
       ls.sel_count = hit.count;
       ls.dens_count = hit.count;
@@ -595,11 +617,12 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
       } else if (hit.count <= td.cand_cap) {
         ls.mode = kSelCand;
         ls.rng_lo = new_lo;
-        ls.rng_hi = new_lo + (1u << shift);
+        ls.rng_hi = new_hi;
         atomicSub(&glob->hist_pending[step_id & 1u], 1u);
       } else {
         const uint32_t ns = shift > (uint32_t)kHistBits ? shift - kHistBits : 0u;
         ls.win_lo = new_lo;
+        ls.win_hi = new_hi;
         ls.win_shift = ns;
         ls.win_bins = 1u << (shift - ns);
       }
@@ -612,10 +635,11 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
 // Fallback radix select: histogram pass over the tensors in histogram mode, each workgroup over
 // its share of the chunk list.  The workgroup that is the last to deliver its part of a tensor's
 // histogram also scans it (select_scan), so no workgroup ever waits for another.  One round is
-// what a tensor normally needs; if the scan still cannot confine the threshold (a predicted
-// window that missed, more keys in the pivot bin than can be listed: at most three more rounds,
-// 11 + 11 + 9 key bits), the same workgroup makes the further passes over the whole tensor on
-// its own -- slow for a large tensor, but rare, and it keeps the fallback to one launch.
+// what a tensor normally needs, and the step launches two (a window that missed, or more keys in
+// the pivot bin than can be listed, needs the second).  Beyond that (a miss followed by
+// refinements, heavy ties: at most four rounds in all) the workgroup that scans makes up to
+// `serial_rounds` further passes over the whole tensor on its own -- slow for a large tensor, but
+// rare, and it bounds the fallback to two launches.
 // Leaves at once when no tensor is in histogram mode: a workgroup that sees the pending count at
 // zero owns no chunk of a tensor still being counted, because a tensor's scan, which alone
 // lowers the count, needs every workgroup owning one of its chunks to have arrived.
@@ -623,7 +647,7 @@ __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, Glob
 __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __restrict__ tds,
                                                         const ChunkRef* __restrict__ chunks, uint32_t total_chunks,
                                                         LayerDev* layers, GlobalDev* glob, uint32_t* hist,
-                                                        StepArg sa) {
+                                                        StepArg sa, int serial_rounds) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   if (__hip_atomic_load(&glob->hist_pending[sc.step_id & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
@@ -663,12 +687,12 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
         if (s_last) {
           __threadfence();  // acquire: the scan below reads what the other workgroups added
           select_scan((uint32_t)cur, td, layers[cur], glob, hist, sc.step_id, s_hist, s_part, s_out, true);
-          for (int extra = 0; extra < 3; ++extra) {
+          for (int extra = 0; extra < serial_rounds; ++extra) {
             if (layers[cur].mode != kSelHist) break;  // written before the barrier that ends the scan
             for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
             __syncthreads();
             // after a scan the number of keys above the window is known
-            const Window w2{layers[cur].win_lo, layers[cur].win_shift, layers[cur].win_bins};
+            const Window w2{layers[cur].win_lo, layers[cur].win_shift, layers[cur].win_bins, layers[cur].win_hi};
             uint32_t unused = 0;
             for (uint32_t q = 0; q < td.n_chunks; ++q) {
               const int64_t b2 = (int64_t)q * kChunk;
@@ -687,7 +711,7 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
       td = tds[t];
       const LayerDev& ls = layers[t];
       active = td.has_probe != 0 && ls.mode == kSelHist && ls.passes > 0;
-      w = Window{ls.win_lo, ls.win_shift, ls.win_bins};
+      w = Window{ls.win_lo, ls.win_shift, ls.win_bins, ls.win_hi};
       count_above = ls.count_above != 0;
       above = 0;
       mine = 0;
@@ -895,6 +919,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   const uint64_t expect = ls.dens_width ? ((uint64_t)(band_hi - band_lo) * ls.dens_count) / ls.dens_width : 0u;
   ls.mode = kSelHist;
   ls.win_lo = lo_bin << s;
+  ls.win_hi = ls.win_lo + ((uint32_t)kHistBins << s);
   ls.win_shift = s;
   ls.win_bins = kHistBins;
   ls.band_lo = band_lo;
@@ -1029,10 +1054,10 @@ hipError_t launch_curv_ema(const DeviceTables& t, const StepArg& sa, float beta_
   return hipSuccess;
 }
 
-hipError_t launch_hist_pass(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
+hipError_t launch_hist_pass(const DeviceTables& t, const StepArg& sa, int serial_rounds, hipStream_t s) {
   const uint32_t grid = t.total_chunks < t.persistent_grid ? t.total_chunks : t.persistent_grid;
   hipLaunchKernelGGL(k_hist_pass, dim3(grid), dim3(kThreads), 0, s, t.tensors, t.chunks, t.total_chunks, t.layers,
-                     t.glob, t.hist, sa);
+                     t.glob, t.hist, sa, serial_rounds);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

@@ -31,7 +31,7 @@ STEP_SOURCES = ("update.hip", "update_body.h", "device_util.h", "numerics.h")
 POWER_SOURCES = ("power.hip", "power.h", "numerics.h")
 MEASURED_TRAFFIC = {
     # k_update<false>, default run of the large_streaming workload
-    "step": {"sources_sha256": "38948805bdac36db298288430170911294a84566ffcac47624e90ec14e5f9726", "workload": "large_streaming",
+    "step": {"sources_sha256": "1d24179a83d2f96c1c1e782a979bfaf51cdd8a86bc295c56e0f805b84788eb52", "workload": "large_streaming",
              "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
     # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
     "power": {"sources_sha256": "5cbb185eadd41b14669fb62e658695710a4237dcda5f869e3390ed3ea3047578", "workload": "large_streaming",

@@ -32,7 +32,7 @@ POWER_SOURCES = ("power.hip", "power.h", "numerics.h")
 MEASURED_TRAFFIC = {
     # k_update<false>, default run of the large_streaming workload
     "step": {"sources_sha256": "1d24179a83d2f96c1c1e782a979bfaf51cdd8a86bc295c56e0f805b84788eb52", "workload": "large_streaming",
-             "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
+             "alg_bytes": 18991808512, "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
     # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
     "power": {"sources_sha256": "5cbb185eadd41b14669fb62e658695710a4237dcda5f869e3390ed3ea3047578", "workload": "large_streaming",
               "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.48e9},
@@ -49,10 +49,12 @@ def sources_digest(files):
     return h.hexdigest()
 
 
-def measured_traffic(workload, all_fp32, n_tensors_limit, variant=False):
-    """Counter-measured HBM bytes per launch of k_update, or None if they do not apply to this run."""
+def measured_traffic(workload, all_fp32, n_tensors_limit, variant, alg_bytes):
+    """Counter-measured HBM bytes per launch of k_update, or None if they do not apply to this run
+    (another workload or variant, or launches that do other work than those of the counter run,
+    e.g. mask passes of tensors that fell back)."""
     m = MEASURED_TRAFFIC["step"]
-    if workload != m["workload"] or all_fp32 or n_tensors_limit or variant:
+    if workload != m["workload"] or all_fp32 or n_tensors_limit or variant or int(alg_bytes) != m["alg_bytes"]:
         return None
     if sources_digest(STEP_SOURCES) != m["sources_sha256"]:
         return None
@@ -306,7 +308,8 @@ def main():
             "unit": "GB/s",
             "frac": upd_gbps / HBM_PEAK_GBPS,
             "alg_bytes_per_launch": dominant_bytes,
-            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise or args.switch_stress),
+            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise or args.switch_stress,
+                                        dominant_bytes),
         },
         "step": {
             "alg_bytes_per_param": total_bytes / N,

@@ -187,14 +187,14 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
   if (elem && any_probe) {
     // element-wise step sizes need the final threshold: finish the mask and the selection first
     TA_HIP(launch_mask_pass(T, sa, s));
-    TA_HIP(launch_select_finish(T, sa, s));
+    TA_HIP(launch_select_finish(T, sa, h->hp.beta_curv, s));
   }
   if (ev) TA_HIP(hipEventRecord(ev[4], s));
   TA_HIP(launch_update(T, sa, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
   if (ev) TA_HIP(hipEventRecord(ev[5], s));
   TA_HIP(launch_update_resize(T, sa, h->cfg.weight_decay, h->cfg.momentum, h->cfg.alpha, elem, s));
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[6], s));
-  if (any_probe && !elem) TA_HIP(launch_select_finish(T, sa, s));
+  if (any_probe && !elem) TA_HIP(launch_select_finish(T, sa, h->hp.beta_curv, s));
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[7], s));
   TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
   return TRIACCEL_OK;

@@ -105,7 +105,8 @@ struct LayerDev {
   uint32_t theta_key_last2;// theta of the probed step before that
   uint32_t n_theta;        // how many thresholds are known (0, 1, 2 = two or more)
   float var_hold;          // running mean squared error (keys^2) of predicting "same as last step"
-  float var_ext;           // same for the linear extrapolation from the last two steps
+  float var_ext;           // same for the damped extrapolation (pred_ext_key)
+  uint32_t pred_ext_key;   // threshold the damped extrapolation expects at the next probed step (0 = none)
   uint32_t band_lo, band_hi;  // keys in [band_lo, band_hi) are listed by the EMA kernel
   uint32_t use_band;       // the EMA kernel writes the provisional mask and lists the band
   uint32_t mask_done;      // the mask needs no separate pass this step

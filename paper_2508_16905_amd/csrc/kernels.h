@@ -30,7 +30,7 @@ hipError_t launch_grad_stats(const DeviceTables& t, const StepArg& sa, hipStream
 hipError_t launch_curv_ema(const DeviceTables& t, const StepArg& sa, float beta_h, float omb_h, int fisher,
                            hipStream_t s);
 hipError_t launch_hist_pass(const DeviceTables& t, const StepArg& sa, int serial_rounds, hipStream_t s);
-hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, hipStream_t s);
+hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, float beta_h, hipStream_t s);
 hipError_t launch_layer(const DeviceTables& t, const StepArg& sa, const Hyper& hp, hipStream_t s);
 hipError_t launch_update(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha, bool elem,
                          hipStream_t s);

@@ -137,8 +137,8 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
 // Threshold selection (exact k-th largest |h_i| per tensor) on the 31-bit magnitude keys,
 // organised so that a probed step normally needs NO pass over h beyond the one that creates it:
 //
-//   * From the thresholds of the two previous probed steps the library predicts this step's
-//     threshold and a BAND around it (a few times the error the last predictions made).
+//   * From the thresholds of the last probed steps (up to three) the library predicts this
+//     step's threshold and a BAND around it (a few times the error the last predictions made).
 //   * The EMA kernel writes a provisional mask (bit = key at or above the band), lists the keys
 //     inside the band, and counts the keys above it.
 //   * If the k-th largest key falls inside the band (count above < k <= count above + listed),
@@ -752,7 +752,7 @@ __device__ __forceinline__ uint32_t finish_block_sum(uint32_t v, uint32_t* s_red
 __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDesc* __restrict__ tds,
                                                                   LayerDev* layers, const GlobalDev* glob,
                                                                   const Candidate* cands, uint32_t* counters,
-                                                                  StepArg sa) {
+                                                                  StepArg sa, float beta_h) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t l = blockIdx.x;
@@ -867,12 +867,15 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
   ls.sel_passes = ls.passes - 1 + (ls.mask_done ? 0u : 1u);  // passes over h beyond the EMA pass
   ls.probes_seen = ls.probes_seen + 1;
   // ---- plan the next probed step ----
-  // Two predictors of the next threshold are tracked by the error each would have made for this
-  // step: "hold" (the last threshold; best when the threshold only jitters) and "extrapolate"
-  // (linear in key space from the last two; best while the curvature EMA is still drifting).
-  // Each keeps a running mean of its squared error (an error three times the running deviation
-  // replaces the mean at once); the predictor with the smaller one is used, and the band is a
-  // multiple of its deviation.
+  // Two predictors of the next threshold are tracked by the error each made for this step:
+  // "hold" (the last threshold; best when the threshold only jitters) and a damped extrapolation
+  // in the value domain, theta + r (theta - prev), best while the curvature EMA still settles:
+  // the distance of the threshold from its limit then shrinks by a nearly constant factor per
+  // probe, so r is the ratio of the last two differences, kept within [0, 1] (between "hold" and
+  // a straight line), and beta_h, the factor by which the EMA forgets, while only two thresholds
+  // are known.  Each predictor keeps a running mean of its squared error in keys (an error three
+  // times the running deviation replaces the mean at once); the one with the smaller mean is
+  // used, and the band is a multiple of its deviation.
   const uint32_t prev2 = ls.theta_key_last2;
   const float unknown2 = (float)kUnknownPredErr * (float)kUnknownPredErr;
   auto track = [](float var, float err, bool first) {
@@ -880,28 +883,37 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
     if (first || e2 > 9.0f * var) return e2;
     return 0.75f * var + 0.25f * e2;
   };
-  float v_hold = unknown2, v_ext = 3.0e38f;
+  float v_hold = unknown2, v_ext = ls.pred_ext_key ? ls.var_ext : 3.0e38f;
   if (have >= 1) v_hold = track(ls.var_hold, (float)abs_diff(theta, prev), have < 2);
-  if (have >= 2) {
-    int64_t p = 2 * (int64_t)prev - (int64_t)prev2;
-    if (p < 0) p = 0;
-    v_ext = track(ls.var_ext, (float)abs_diff(theta, (uint32_t)p), !(ls.var_ext < 3.0e38f));
-  }
+  if (ls.pred_ext_key) v_ext = track(v_ext, (float)abs_diff(theta, ls.pred_ext_key), !(v_ext < 3.0e38f));
   if (ls.window_missed) {
     v_hold = fmaxf(v_hold, unknown2);
     if (v_ext < 3.0e38f) v_ext = fmaxf(v_ext, unknown2);
   }
+  uint32_t ext = 0;
+  if (have >= 1) {
+    const double v0 = (double)u2f(theta), v1 = (double)u2f(prev);
+    const double d1 = v0 - v1;
+    double r = (double)beta_h;
+    if (have >= 2) {
+      const double d0 = v1 - (double)u2f(prev2);
+      r = d0 != 0.0 ? d1 / d0 : 1.0;
+    }
+    r = fmin(fmax(r, 0.0), 1.0);
+    const float p = (float)(v0 + r * d1);
+    ext = p > 0.0f ? min(max(f2u(p), 1u), 0x7f7fffffu) : 1u;
+  }
   ls.var_hold = v_hold;
   ls.var_ext = v_ext;
+  ls.pred_ext_key = ext;
   ls.theta_key_last2 = prev;
   ls.theta_key_last = theta;
   ls.n_theta = have < 2 ? have + 1 : 2;
-  const bool extrapolate = have >= 1 && v_ext < v_hold;
+  const bool extrapolate = ext != 0u && v_ext < v_hold;
   // e: 1.5 deviations of the chosen predictor (band = 3 e = 4.5 deviations, window half = 32 e)
   const float dev = 1.5f * sqrtf(extrapolate ? v_ext : v_hold);
   const uint32_t e = dev < 16.0f ? 16u : (dev > 1.0e9f ? 1000000000u : (uint32_t)dev);
-  int64_t centre = (int64_t)theta;
-  if (extrapolate) centre += (int64_t)theta - (int64_t)prev;
+  int64_t centre = extrapolate ? (int64_t)ext : (int64_t)theta;
   if (centre < 1) centre = 1;
   if (centre > 0x7f7fffff) centre = 0x7f7fffff;
   // fallback window: 2048 bins whose half (1024 bins) spans 32 e
@@ -1062,9 +1074,9 @@ hipError_t launch_hist_pass(const DeviceTables& t, const StepArg& sa, int serial
   return hipSuccess;
 }
 
-hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, hipStream_t s) {
+hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, float beta_h, hipStream_t s) {
   hipLaunchKernelGGL(k_select_finish, dim3(t.n_tensors), dim3(kFinishThreads), 0, s, t.tensors, t.layers, t.glob,
-                     t.cands, t.cand_counters, sa);
+                     t.cands, t.cand_counters, sa, beta_h);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

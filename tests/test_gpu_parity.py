@@ -383,3 +383,22 @@ def test_every_outcome_of_the_band_check_is_reached_with_parity():
         run(t)
     assert {1, 2, 3, 4, 5} <= seen[0], seen
     p.close()
+
+
+def test_threshold_prediction_settles_within_a_few_probes():
+    """With a fresh probe every step the predicted band must take over early in a run (diagnostic
+    code 1 of the layer record: no pass over h beyond the one that creates it).  Steps 1-3 have no
+    usable prediction; after that an occasional miss is allowed (the first error estimates rest on
+    one or two samples).  Every step is compared with the oracle as well."""
+    sizes = [300007, 1100003]
+    wl = custom(sizes, name="large_streaming", steps=24)
+    p = Pair(wl)
+    held = [0] * len(sizes)
+    for t in range(1, 25):
+        g, z, hz = p.inputs(t)
+        p.step(g, z, hz, label=f"t={t}")
+        if t >= 5:
+            for l, s in enumerate(p.gpu.layer_state()):
+                held[l] += int(s.sel_outcome) == 1
+    p.close()
+    assert all(h >= 15 for h in held), held   # of 20 steps

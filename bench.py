@@ -316,6 +316,9 @@ def main():
             "alg_GB": total_bytes / 1e9,
             "GBps": step_gbps,
             "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
+            # HIP-event time from the first to the last kernel of a step, median over the steps of
+            # the stage breakdown (an event at every stage boundary costs the stream a few microseconds)
+            "ms_events_median": sorted(sum(s) for s in stage_ms)[KP // 2],
         },
         "stages": stages,
     }

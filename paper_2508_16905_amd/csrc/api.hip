@@ -354,7 +354,6 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   T.total_chunks = (uint32_t)chunks.size();
   T.max_chunks_per_tensor = max_chunks;
   T.persistent_grid = cus * 8;
-  T.fallback_grid = cus * 4;
   if ((rc = dev_alloc(c, &T.tensors, (size_t)n))) return fail(rc);
   if ((rc = dev_alloc(c, &T.chunks, chunks.size()))) return fail(rc);
   if ((rc = dev_alloc(c, &T.partials, chunks.size()))) return fail(rc);

@@ -23,7 +23,6 @@ struct DeviceTables {
   uint32_t total_chunks;
   uint32_t max_chunks_per_tensor;
   uint32_t persistent_grid;  // workgroups of the persistent streaming kernels
-  uint32_t fallback_grid;    // workgroups of the rarely-needed passes
 };
 
 hipError_t launch_grad_stats(const DeviceTables& t, const StepArg& sa, hipStream_t s);

@@ -123,6 +123,24 @@ def test_dependent_and_zero_vectors_are_flagged_and_zeroed():
     assert np.max(np.abs(g - np.eye(2))) < 1e-6
 
 
+def test_rank_threshold_separates_rounding_from_a_small_but_real_direction():
+    # remainder^2 <= 1e-12 ||Hu||^2 means "no direction left".  A second vector that differs from the
+    # first by a relative 1e-4 (remainder^2 / norm^2 = 1e-8) is nearly parallel but still carries a
+    # direction and must be kept and orthonormalised; one that differs by 1e-7 (1e-14) must be flagged.
+    n = 64
+    e0, e1 = np.zeros(n), np.zeros(n)
+    e0[0], e1[1] = 1.0, 1.0
+    u = np.ones((2, n), dtype=np.float32)
+    for eps, flagged in ((1e-4, False), (1e-7, True)):
+        hu = np.stack([e0, e0 + eps * e1]).astype(np.float32)
+        out, _, _, _, d = power_step(u, hu)
+        assert d == (0b10 if flagged else 0)
+        if flagged:
+            assert not out[1].any()
+        else:
+            assert abs(abs(out[1][1]) - 1.0) < 1e-6 and abs(out[1][0]) < 1e-6
+
+
 def test_latched_lambda_feeds_the_step_size_and_the_promotion():
     rng = np.random.default_rng(9)
     n = 40

@@ -136,3 +136,103 @@ def test_tiny_mlp_workload_acceptance():
         diag = wl.hessian_diagonal(l)
         assert not (t.mask_bits() & (diag == 0)).any()
         assert t.nnz > 0
+
+
+# ---- sequencing pins on small hand-made cases (plain numpy beside the oracle) ----
+
+def _small(cfg_kw, n=64, dtype=FP32, seed=0):
+    rng = np.random.default_rng(seed)
+    cfg = oracle.OracleConfig(**cfg_kw)
+    p = rng.standard_normal(n).astype(np.float32)
+    return oracle.OracleTriAccel(cfg, [p], [dtype], [FP32]), p, rng
+
+
+def test_variance_ema_starts_at_the_first_applied_step_also_after_a_skipped_one():
+    # constant per-step variance is a fixed point of the EMA from the first applied step on (Sec. 3.1)
+    orc, _, rng = _small(dict(beta_var=0.9))
+    g = rng.standard_normal(64).astype(np.float32)
+    bad = g.copy()
+    bad[3] = np.inf
+    assert orc.step([bad], [None], [None], 0.1, 1.0, 96, 0, 100)["skipped"] == 1
+    want = np.float32(np.var(g.astype(np.float64)))
+    for _ in range(3):
+        assert orc.step([g], [None], [None], 0.1, 1.0, 96, 0, 100)["skipped"] == 0
+        assert orc.tensors[0].v == want and orc.tensors[0].var == want
+
+
+def test_first_probe_initialises_whenever_it_arrives():
+    # a diagonal Hessian gives z * Hz = diag(H) exactly; the first probe sets h to it even when the
+    # run started without probes, the second one is a fixed point of the EMA
+    orc, _, rng = _small(dict(beta_curv=0.9))
+    g = rng.standard_normal(64).astype(np.float32)
+    diag = rng.uniform(0.5, 2.0, 64).astype(np.float32)
+    orc.step([g], [None], [None], 0.1, 1.0, 96, 0, 100)
+    for _ in range(2):
+        z = rng.choice([-1.0, 1.0], 64).astype(np.float32)
+        orc.step([g], [z], [diag * z], 0.1, 1.0, 96, 0, 100)
+        assert np.allclose(orc.tensors[0].curv, diag, rtol=2e-7, atol=0)
+    orc2, _, _ = _small(dict(beta_curv=0.9))
+    z = rng.choice([-1.0, 1.0], 64).astype(np.float32)
+    orc2.step([g], [None], [None], 0.1, 1.0, 96, 0, 100)
+    orc2.step([g], [z], [diag * z], 0.1, 1.0, 96, 0, 100)
+    assert np.array_equal(orc2.tensors[0].curv, diag)
+
+
+def test_loss_scale_divides_out():
+    # a power-of-two loss scale is removed exactly: same state as the unscaled run
+    kw = dict(alpha=0.5, tau_low=1e-3, tau_high=1e3)
+    a, _, rng = _small(kw)
+    b, _, _ = _small(kw)
+    for _ in range(3):
+        g = rng.standard_normal(64).astype(np.float32)
+        z = rng.choice([-1.0, 1.0], 64).astype(np.float32)
+        hz = rng.standard_normal(64).astype(np.float32)
+        a.step([g], [z], [hz], 0.1, 1.0, 96, 0, 100)
+        b.step([g * np.float32(1024)], [z], [hz * np.float32(1024)], 0.1, 1024.0, 96, 0, 100)
+    assert same(snapshot(a), snapshot(b))
+
+
+def test_stored_precision_of_the_previous_step_is_what_the_next_step_reads():
+    # thresholds force FP16 storage from the first step on, although the tensor starts as FP32:
+    # step 2 must widen FP16 values.  Plain SGD (no momentum, no decay, alpha = 0) beside it in numpy.
+    orc, p, rng = _small(dict(tau_low=1e30, tau_high=2e30, tau_curv=1e30, alpha=0.0, momentum=0.0,
+                              weight_decay=0.0))
+    ref = p.copy()
+    for step in range(3):
+        g = rng.standard_normal(64).astype(np.float32)
+        orc.step([g], [None], [None], 0.1, 1.0, 96, 0, 100)
+        t = orc.tensors[0]
+        assert (t.prev_code, t.code) == ((FP32 if step == 0 else FP16), FP16)
+        ref = (ref - np.float32(0.1) * g).astype(np.float16).astype(np.float32)
+        got = t.param_f32()
+        # fma vs separate rounding may differ in the last fp16 place on rare elements
+        assert np.max(np.abs(got - ref)) <= np.max(np.abs(ref)) * 2.0 ** -10
+        assert np.mean(got == ref) > 0.95
+
+
+def test_control_interval_counts_applied_steps():
+    # T_ctrl = 2 with the second call skipped: the control steps are the 2nd and 4th APPLIED steps,
+    # i.e. calls 3 and 5 (a skipped step changes no state, counters included)
+    orc, _, rng = _small(dict(ctrl_interval=2, tau_low=1e30, tau_high=2e30, tau_curv=1e30))
+    codes = []
+    for call in range(1, 6):
+        g = rng.standard_normal(64).astype(np.float32)
+        if call == 2:
+            g[0] = np.nan
+        orc.step([g], [None], [None], 0.1, 1.0, 96, 0, 100)
+        codes.append(orc.tensors[0].code)
+    assert codes == [FP32, FP32, FP16, FP16, FP16]
+
+
+def test_first_fisher_sample_initialises_whenever_it_arrives():
+    # squared-gradient source with the curvature refresh switched off at the first step: the first
+    # refresh sets h to the sample itself, the next one smooths
+    orc, _, rng = _small(dict(curvature_source=1, beta_curv=0.9))
+    g1, g2, g3 = (rng.standard_normal(64).astype(np.float32) for _ in range(3))
+    orc.step([g1], [None], [None], 0.1, 1.0, 96, 0, 100, update_curvature=False)
+    assert not orc.tensors[0].curv.any() and orc.tensors[0].nnz == 0
+    orc.step([g2], [None], [None], 0.1, 1.0, 96, 0, 100, update_curvature=True)
+    assert np.array_equal(orc.tensors[0].curv, g2 * g2)
+    orc.step([g3], [None], [None], 0.1, 1.0, 96, 0, 100, update_curvature=True)
+    want = 0.9 * (g2.astype(np.float64) ** 2) + 0.1 * (g3.astype(np.float64) ** 2)
+    assert np.allclose(orc.tensors[0].curv, want, rtol=1e-6, atol=0)

@@ -406,7 +406,7 @@ def bench_power(args, wl, hyper, dev):
 def cpu_baseline(wl, hyper, first_set, n_sample, scale):
     """The CPU oracle, as it stands, timed on a bounded sample of the same workload: the first tensors
     up to about 1.5e8 parameters (the whole workload when it is smaller), as many steps as fit in
-    about two seconds of wall time."""
+    about six seconds of wall time (twice: all cores, then one thread)."""
     import oracle
     from _runner import to_numpy
 
@@ -427,7 +427,7 @@ def cpu_baseline(wl, hyper, first_set, n_sample, scale):
             orc.step(gs, zs, hzs, *args)
             steps += 1
             dt = time.perf_counter() - t0
-            if dt >= 2.0 or steps >= 200:
+            if dt >= 6.0 or steps >= 2000:
                 return steps, dt
 
     orc = oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx), workers=cores)

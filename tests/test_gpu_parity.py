@@ -402,3 +402,30 @@ def test_threshold_prediction_settles_within_a_few_probes():
                 held[l] += int(s.sel_outcome) == 1
     p.close()
     assert all(h >= 15 for h in held), held   # of 20 steps
+
+
+@pytest.mark.parametrize("seed", [5, 23, 27, 28])
+def test_selection_under_ties_zeros_and_jumps(seed):
+    """Multi-million-element tensors whose curvature samples are, at random steps, rescaled by
+    orders of magnitude, quantised (many equal magnitudes) or mostly zero, with sparsity targets from
+    0 to 100 % or a fixed k: the threshold selection leaves its predicted band in every direction and
+    every step is still compared with the oracle."""
+    rs = np.random.default_rng(7000 + seed)
+    sizes = [int(rs.integers(9000, 3_000_000)) for _ in range(int(rs.integers(1, 4)))]
+    hyper = dict(sparsity_ppm=int(rs.choice([0, 10, 500000, 950000, 999990, 1000000])), tau_curv=1e30)
+    if rs.integers(0, 3) == 0:
+        hyper = dict(topk_abs=int(rs.choice([1, 5, 70000, 400000])), tau_curv=1e30)
+    wl = custom(sizes, name=str(rs.choice(["resnet18", "large_streaming"])), steps=16, seed=900 + seed, **hyper)
+    p = Pair(wl)
+    for t in range(1, 17):
+        g, z, hz = p.inputs(t)
+        kind = int(rs.integers(0, 6))
+        if kind == 1:
+            hz = [x * float(rs.choice([1e-3, 0.05, 20.0, 1e3])) for x in hz]
+        elif kind == 2:
+            hz = [torch.round(x * 4.0) / 4.0 for x in hz]
+        elif kind == 3:
+            hz = [torch.where(torch.from_numpy(rs.uniform(size=x.numel()) < 0.02).reshape(x.shape), x,
+                              torch.zeros_like(x)) for x in hz]
+        p.step(g, z, hz, label=f"seed {seed} t={t} kind={kind}")
+    p.close()

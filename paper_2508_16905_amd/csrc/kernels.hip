@@ -4,9 +4,6 @@
 // lane holding 4 consecutive elements (one 128-bit access per lane, row and fp32 array).  All
 // arithmetic that decides a stored value is fp32 with an explicit operation order (fmaf where a
 // fused multiply-add is meant; the file is compiled with -ffp-contract=off); reductions are fp64.
-
-
-
 #include "device_util.h"
 
 namespace triaccel {

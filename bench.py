@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--switch-stress", action="store_true",
                     help="variance EMA off and a gradient scale cycling over three decades: every layer changes "
                          "its storage precision at every step (all updates go through the in-place resize)")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="timed steps carry no curvature probe (the ordinary step between two curvature refreshes, "
+                         "Sec. 4.1: T = 200); settle and warm-up steps still probe")
     ap.add_argument("--settle", type=int, default=64,
                     help="the optimizer state is first brought to at least this many steps into the run (untimed, "
                          "before the warm-up steps): the exact threshold needs no second pass over the curvature "
@@ -201,10 +204,12 @@ def main():
         opt.set_profiling(1 if args.switch_stress else 2)
     lr = float(hyper["lr"])
 
-    def one(i):
+    def one(i, probe=True):
         g, z, hz = sets[i % R]
+        if not probe:
+            z = hz = None
         opt.step(g, z, hz, lr=lr, loss_scale=scale, batch_size=int(hyper["batch_size"]),
-                 mem_used_bytes=8, mem_total_bytes=10)
+                 mem_used_bytes=8, mem_total_bytes=10, update_curvature=probe)
 
     # bring the run to its steady state first when the warm-up alone is shorter than that takes
     P = max(0, args.settle - W)
@@ -218,8 +223,9 @@ def main():
     codes_before = [s.code for s in opt.layer_state()]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    probed = not args.no_probe
     for i in range(P + W, P + W + K):
-        one(i)
+        one(i, probed)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -232,7 +238,7 @@ def main():
     # every stage boundary (not part of the timed region)
     opt.set_profiling(1)
     for i in range(P + W + K, P + W + K + KP):
-        one(i)
+        one(i, probed)
     opt.result()
     state = opt.layer_state()
     codes = [s.code for s in state]
@@ -244,7 +250,7 @@ def main():
     # unless a layer switched; the count of switches is reported)
     switched = sum(1 for a, b in zip(codes_before, codes) if a != b)
     sel_passes = [s.sel_passes for s in state]
-    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, True, hyper["momentum"] != 0.0,
+    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, hyper["momentum"] != 0.0,
                             fisher=args.fisher, elem=args.elementwise)
     total_bytes = sum(alg.values())
     # bytes each kernel stage actually has to move in the last timed step
@@ -284,7 +290,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{wl.name}: {L} tensors, {N} params, fp{8 * grad_size} gradients, probe every step, "
+            "workload": f"{wl.name}: {L} tensors, {N} params, fp{8 * grad_size} gradients, "
+                        f"{'probe every step' if probed else 'no probe in the timed steps'}, "
                         f"momentum {hyper['momentum']}, sparsity {hyper['sparsity_ppm'] / 1e4:.0f}%",
             "all_fp32": bool(args.all_fp32),
             "step_size": "per element" if args.elementwise else "per layer",

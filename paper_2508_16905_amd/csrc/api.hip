@@ -748,7 +748,7 @@ int triaccel_power_times_get(triaccel_handle h, float* ms) {
 
 int triaccel_cast_f32(const float* src, void* dst, int64_t n, int32_t dtype, void* hip_stream) {
   if (!src || !dst) return TRIACCEL_E_NULL_PTR;
-  if (n < 0) return TRIACCEL_E_INVALID_ARG;
+  if (n < 0 || n > (int64_t)0x7fffffff * kChunk) return TRIACCEL_E_INVALID_ARG;  // one workgroup per chunk
   if (!valid_dtype(dtype)) return TRIACCEL_E_BAD_DTYPE;
   if (!aligned16(src) || !aligned16(dst)) return TRIACCEL_E_ALIGNMENT;
   if (n == 0) return TRIACCEL_OK;

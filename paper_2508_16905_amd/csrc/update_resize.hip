@@ -76,11 +76,23 @@ __global__ __launch_bounds__(kSerialParts * kThreads) void k_update_resize(
 // ---------------------------------------------------------------------------------------------
 template <int ND>
 __global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src, void* dst, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads * kVec;
-  for (int64_t idx = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * kVec; idx < n; idx += stride) {
-    float v[4];
-    load4_guard<kFP32>(src, idx, n, 0.0f, v);
-    store4_guard<ND>(dst, idx, n, v);
+  // same shape as the step kernels: one workgroup per chunk, all loads of the chunk before its stores
+  const int64_t base = (int64_t)blockIdx.x * kChunk;
+  float v[kRows][4];
+  if (base + kChunk <= n) {
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) load4<kFP32>(src, base + r * kRowElems + (int64_t)threadIdx.x * kVec, v[r]);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) store4<ND>(dst, base + r * kRowElems + (int64_t)threadIdx.x * kVec, v[r]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+      const int64_t idx = base + r * kRowElems + (int64_t)threadIdx.x * kVec;
+      if (idx < n) {
+        load4_guard<kFP32>(src, idx, n, 0.0f, v[r]);
+        store4_guard<ND>(dst, idx, n, v[r]);
+      }
+    }
   }
 }
 
@@ -129,8 +141,7 @@ void set_scalars_node_params(hipKernelNodeParams* p, void** args, const StepScal
 }
 
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dtype, hipStream_t s) {
-  int64_t blocks = (n + kThreads * kVec - 1) / (kThreads * kVec);
-  if (blocks > 65536) blocks = 65536;
+  int64_t blocks = (n + kChunk - 1) / kChunk;
   if (blocks < 1) blocks = 1;
   switch (dtype) {
     case kFP32: hipLaunchKernelGGL(k_cast<kFP32>, dim3((uint32_t)blocks), dim3(kThreads), 0, s, src, dst, n); break;

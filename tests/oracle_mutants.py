@@ -1,10 +1,15 @@
 """Mutation check of the oracle's pins (CPU only; not collected by pytest -- run it by hand:
-``python tests/oracle_mutants.py [-j 8] [indices...]``, about twenty minutes on eight cores).
+``python tests/oracle_mutants.py [-j 8] [--gpu] [--logdir DIR] [indices...]``, about twenty minutes on eight cores).
 
 Each entry plants ONE plausible mistake in a private copy of the oracle (a dropped term, a wrong
 sign or comparison, swapped operands, an off-by-one, a wrong counter) and runs the CPU tests of the
-oracle against that copy.  A mutant that no test notices points at a missing pin.  Nothing here
-touches the HIP library or a GPU; the repository's own files are never modified."""
+oracle against that copy.  A mutant that no test notices points at a missing pin.  The
+repository's own files are never modified.
+
+With ``--gpu`` (on a machine with an MI355X) the mutated oracle is instead put beside the
+UNCHANGED HIP library and the GPU parity tests are run: every mutant must make them fail, which
+shows that those tests really compare what the oracle computes (the mistake is in the oracle, on
+the CPU; the GPU code runs as built)."""
 import os
 import shutil
 import subprocess
@@ -90,6 +95,10 @@ M = [
 ]
 
 
+GPU = False
+LOGDIR = None
+
+
 def check(idx):
     f, a, b = M[idx]
     src = open(os.path.join(ROOT, f)).read()
@@ -103,11 +112,24 @@ def check(idx):
                             ignore=shutil.ignore_patterns("__pycache__", "*.so"))
         with open(os.path.join(tree, f), "w") as fh:
             fh.write(src.replace(a, b, 1))
-        tests = sorted("tests/" + t for t in os.listdir(os.path.join(tree, "tests"))
-                       if t.startswith("test_oracle_") or t == "test_workloads.py")
-        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + tests, cwd=tree,
-                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        where = [l for l in r.stdout.splitlines() if "Error" in l or "FAILED" in l][:1]
+        if GPU:
+            os.symlink(os.path.join(ROOT, "paper_2508_16905_amd"), os.path.join(tree, "paper_2508_16905_amd"))
+            tests = ["-m", "gpu", "--timeout", "300", "--timeout-method", "thread", "tests/test_gpu_parity.py",
+                     "tests/test_gpu_power.py"]
+        else:
+            tests = sorted("tests/" + t for t in os.listdir(os.path.join(tree, "tests"))
+                           if t.startswith("test_oracle_") or t == "test_workloads.py")
+        cmd = [sys.executable, "-u", "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + tests
+        if LOGDIR:
+            # the run's own output goes to a file as it is produced (a long GPU run stays visibly alive)
+            log = os.path.join(LOGDIR, f"mutant_{idx}.log")
+            with open(log, "w") as fh:
+                r = subprocess.run(cmd + ["-v"], cwd=tree, stdout=fh, stderr=subprocess.STDOUT, text=True)
+            out = open(log).read()
+        else:
+            r = subprocess.run(cmd, cwd=tree, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+            out = r.stdout
+        where = [l for l in out.splitlines() if "Error" in l or "FAILED" in l][:1]
         return idx, "killed" if r.returncode != 0 else "SURVIVED", label, where[0][:100] if where else ""
     finally:
         shutil.rmtree(tree, ignore_errors=True)
@@ -116,15 +138,25 @@ def check(idx):
 def main():
     args = sys.argv[1:]
     jobs = 8
+    global GPU, LOGDIR
     if args[:1] == ["-j"]:
         jobs, args = int(args[1]), args[2:]
+    if args[:1] == ["--gpu"]:
+        GPU, args = True, args[1:]
+    if args[:1] == ["--logdir"]:
+        LOGDIR, args = os.path.abspath(args[1]), args[2:]
+        os.makedirs(LOGDIR, exist_ok=True)
     todo = [int(x) for x in args] or list(range(len(M)))
     survivors = []
+    from concurrent.futures import as_completed
+
     with ThreadPoolExecutor(jobs) as pool:
-        for idx, verdict, label, where in pool.map(check, todo):
+        for fut in as_completed([pool.submit(check, i) for i in todo]):
+            idx, verdict, label, where = fut.result()
             print(idx, verdict, "|", label, "|", where, flush=True)
             if verdict != "killed":
                 survivors.append(idx)
+    survivors.sort()
     print(f"{len(todo) - len(survivors)} of {len(todo)} mutants killed; survivors: {survivors}")
     return 1 if survivors else 0
 

@@ -429,3 +429,30 @@ def test_selection_under_ties_zeros_and_jumps(seed):
                               torch.zeros_like(x)) for x in hz]
         p.step(g, z, hz, label=f"seed {seed} t={t} kind={kind}")
     p.close()
+
+
+def test_decisions_at_exact_thresholds():
+    """Eq. 2 and the promotion rule at equality (Sec. 3.1, 3.2): v = tau_low gives BF16, v = tau_high
+    gives FP32, lambda = tau_curv does not promote, one ulp above it does.  The inputs make the
+    statistics exact on both sides: gradients +-c (mean 0, variance c^2, a power of two) and a
+    diagonal Hessian whose largest entry is the threshold itself."""
+    n = 8192
+    tau_curv = np.float32(0.5)
+    wl = custom([n] * 4, steps=2, tau_low=2.0 ** -12, tau_high=2.0 ** -10, tau_curv=float(tau_curv),
+                sparsity_ppm=900000, param_dtypes=[FP32] * 4)
+    p = Pair(wl)
+    sign = torch.where(torch.arange(n) % 2 == 0, 1.0, -1.0).to(torch.float32)
+    c = [2.0 ** -6, 2.0 ** -5, 2.0 ** -7, 2.0 ** -7]                  # variances 2^-12, 2^-10, 2^-14, 2^-14
+    dmax = [0.25, 0.25, float(tau_curv), float(np.nextafter(tau_curv, np.float32(1.0)))]
+    rs = np.random.default_rng(11)
+    for t in (1, 2):
+        g = [sign * ci for ci in c]
+        z = [torch.from_numpy(rs.choice([-1.0, 1.0], n).astype(np.float32)) for _ in range(4)]
+        d = [torch.linspace(0.0, 1.0, n, dtype=torch.float32) * dm for dm in dmax]   # last entry = dmax exactly
+        p.step(g, z, [zi * di for zi, di in zip(z, d)], label=f"t={t}", margin_check=False)
+        o = p.orc.tensors
+        assert [float(x.v) for x in o] == [2.0 ** -12, 2.0 ** -10, 2.0 ** -14, 2.0 ** -14]
+        if t == 1:   # the first probe sets h to the diagonal itself
+            assert [float(x.lam) for x in o] == dmax
+            assert [x.code for x in o] == [BF16, FP32, FP16, BF16]
+    p.close()

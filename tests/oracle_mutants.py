@@ -114,8 +114,12 @@ def check(idx):
             fh.write(src.replace(a, b, 1))
         if GPU:
             os.symlink(os.path.join(ROOT, "paper_2508_16905_amd"), os.path.join(tree, "paper_2508_16905_amd"))
-            tests = ["-m", "gpu", "--timeout", "300", "--timeout-method", "thread", "tests/test_gpu_parity.py",
-                     "tests/test_gpu_power.py"]
+            # the quick parity tests (each a few seconds) that between them touch every part of the step
+            quick = ("tiny_mlp or ragged or mixed_state or control_interval or no_momentum or half_precision or "
+                     "skip_step or nonfinite_probe or fisher or elementwise_step or exact_thresholds or fixed_top_k or "
+                     "batch_rule_trace or arrives_after or skipped_first_call")
+            tests = ["-m", "gpu", "--timeout", "300", "--timeout-method", "thread", "-k", quick + " or power",
+                     "tests/test_gpu_parity.py", "tests/test_gpu_power.py"]
         else:
             tests = sorted("tests/" + t for t in os.listdir(os.path.join(tree, "tests"))
                            if t.startswith("test_oracle_") or t == "test_workloads.py")

@@ -456,3 +456,51 @@ def test_decisions_at_exact_thresholds():
             assert [float(x.lam) for x in o] == dmax
             assert [x.code for x in o] == [BF16, FP32, FP16, BF16]
     p.close()
+
+
+def test_batch_rule_trace_through_the_step():
+    # the hand-traced sequence of the memory-elastic batch rule (Sec. 3.3; tests/golden), fed through
+    # triaccel_step's memory arguments: equality at both thresholds, both clamps
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "batch_rule_trace.txt")
+    rows = [tuple(int(x) for x in line.split()) for line in open(path) if line.strip() and not line.startswith("#")]
+    wl = custom([4097], steps=len(rows), rho_low=0.70, rho_high=0.90, delta_up=16, delta_down=32, b_min=16, b_max=160)
+    p = Pair(wl)
+    for t, (b, used, want) in enumerate(rows, start=1):
+        g, z, hz = p.inputs(t)
+        p.batch = b
+        res = p.step(g, z, hz, mem=(used, 1000), label=f"row {t}")
+        assert res["next_batch_size"] == want == p.gpu.result().next_batch_size
+    p.close()
+
+
+@pytest.mark.parametrize("fisher", [False, True])
+def test_first_curvature_sample_arrives_after_the_first_steps(fisher):
+    # two steps without any curvature refresh, then refreshes: the first one initialises h with the
+    # sample itself, whatever the step count
+    wl = custom([5000, 70001], steps=6, curvature_source=int(fisher))
+    p = Pair(wl)
+    for t in range(1, 7):
+        probe = t >= 3
+        g, z, hz = p.inputs(t, probe=probe and not fisher)
+        p.step(g, z, hz, update_curvature=probe, label=f"t={t}")
+        if t == 2:
+            assert all(o.nnz == 0 and not o.curv.any() for o in p.orc.tensors)
+    assert all(o.nnz > 0 for o in p.orc.tensors)
+    p.close()
+
+
+def test_skipped_first_call_and_control_interval_in_applied_steps():
+    # the very first call overflows, and so does the fourth: the variance EMA starts at the first
+    # APPLIED step and the control interval (T_ctrl = 2) counts applied steps only
+    wl = custom([4097, 33, 20000], steps=8, ctrl_interval=2, growth_interval=3)
+    p = Pair(wl)
+    for t in range(1, 9):
+        g, z, hz = p.inputs(t)
+        if t in (1, 4):
+            g[t % 3] = g[t % 3].clone()
+            g[t % 3][7] = float("inf")
+        res = p.step(g, z, hz, label=f"t={t}")
+        assert res["skipped"] == int(t in (1, 4))
+    assert p.orc.applied_steps == 6
+    p.close()

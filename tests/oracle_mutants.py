@@ -156,9 +156,9 @@ def main():
 
     with ThreadPoolExecutor(jobs) as pool:
         for fut in as_completed([pool.submit(check, i) for i in todo]):
-            idx, verdict, label, where = fut.result()
-            print(idx, verdict, "|", label, "|", where, flush=True)
-            if verdict != "killed":
+            idx, outcome, label, where = fut.result()
+            print(idx, outcome, "|", label, "|", where, flush=True)
+            if outcome != "killed":
                 survivors.append(idx)
     survivors.sort()
     print(f"{len(todo) - len(survivors)} of {len(todo)} mutants killed; survivors: {survivors}")

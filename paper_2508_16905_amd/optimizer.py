@@ -114,8 +114,9 @@ class TriAccel:
         """Replay the step as a HIP graph instead of launching its kernels one by one."""
         B.triaccel_set_graph(self.handle, on)
 
-    def set_profiling(self, on: bool) -> None:
-        B.triaccel_set_profiling(self.handle, on)
+    def set_profiling(self, level: int) -> None:
+        """0 off; 1 a HIP event at every stage boundary; 2 events around the update kernel only."""
+        B.triaccel_set_profiling(self.handle, int(level))
 
     def stage_times(self, steps_back: int = 0):
         return B.triaccel_stage_times_get(self.handle, steps_back)

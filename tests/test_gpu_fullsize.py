@@ -40,6 +40,7 @@ def run_sampled(wl, sample, steps, dev, check_all_every=1, fisher=False):
     L = wl.n_tensors
     params = [wl.init_param(l, device=dev) for l in range(L)]
     opt = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype)
+    opt.set_profiling(2)   # the launch configuration that bench.py times: kernel by kernel, events around the update
     cfg = oracle.OracleConfig.from_hyper(wl.hyper)
     orc = oracle.OracleTriAccel(cfg, [to_numpy(params[l]) for l in sample], [wl.init_dtype(l) for l in sample],
                                 [wl.grad_dtype] * len(sample), workers=len(sample))

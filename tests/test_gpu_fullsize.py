@@ -47,6 +47,7 @@ def run_sampled(wl, sample, steps, dev, check_all_every=1, fisher=False):
     del params
     scale, batch = float(wl.hyper["loss_scale"]), int(wl.hyper["batch_size"])
     skipped_steps = []
+    run_sampled.band_steps = 0   # (sampled tensor, step) pairs that the predicted band settled
     for t in range(1, steps + 1):
         grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
         if fisher:
@@ -67,6 +68,7 @@ def run_sampled(wl, sample, steps, dev, check_all_every=1, fisher=False):
         assert res.next_loss_scale == ro["next_loss_scale"] and res.next_batch_size == ro["next_batch_size"]
         skipped_steps.append(res.skipped)
         st = opt.layer_state()
+        run_sampled.band_steps += sum(1 for l in sample if st[l].sel_outcome == 1 and not res.skipped)
         for o, l in zip(orc.tensors, sample):
             g = st[l]
             w = f"{wl.name} step {t} tensor {l}"
@@ -98,8 +100,11 @@ def run_sampled(wl, sample, steps, dev, check_all_every=1, fisher=False):
 def test_large_streaming_full_size_sampled_tensors():
     wl = get_workload("large_streaming")
     assert wl.total_params == 1073741824
-    skipped, codes = run_sampled(wl, sample=[0, 37, 63], steps=3, dev=torch.device("cuda:0"))
-    assert skipped == [0, 0, 0] and len(set(codes)) >= 2
+    # steps 1-3 go through the fallback selection (no prediction yet), the later ones through the
+    # predicted band: both at the full size
+    skipped, codes = run_sampled(wl, sample=[0, 37, 63], steps=6, dev=torch.device("cuda:0"))
+    assert skipped == [0] * 6 and len(set(codes)) >= 2
+    assert run_sampled.band_steps >= 3
 
 
 def test_large_streaming_full_size_fisher_source_and_elementwise_step_size():

@@ -659,7 +659,7 @@ __global__ __launch_bounds__(kThreads) void k_hist_pass(const TensorDesc* __rest
   const uint32_t c1 = min(c0 + per, total_chunks);
   int cur = -1;
   bool active = false;
-  Window w{0, 0, 0};
+  Window w{0, 0, 0, 0};
   TensorDesc td;
   bool count_above = false;  // the number of keys above the window is not known yet (predicted window)
   uint32_t above = 0;

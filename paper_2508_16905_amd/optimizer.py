@@ -3,7 +3,6 @@ C ABI.  PyTorch is used for device memory and the stream only; no arithmetic hap
 
 from __future__ import annotations
 
-import ctypes as C
 from typing import List, Optional, Sequence
 
 import torch

@@ -14,7 +14,6 @@ import numpy as np
 import torch
 
 import paper_2508_16905_amd as ta
-from workloads.configs import TORCH_DTYPE
 from _runner import make_oracle, to_numpy
 
 STAT_RTOL = 1e-5

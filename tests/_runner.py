@@ -3,7 +3,6 @@ import numpy as np
 import torch
 
 import oracle
-from workloads.configs import FP32
 
 
 def to_numpy(t: torch.Tensor) -> np.ndarray:

@@ -2,14 +2,12 @@
 call to call, results are deterministic, several handles coexist, profiling returns stage times."""
 import ctypes as C
 
-import numpy as np
 import pytest
 import torch
 
 import paper_2508_16905_amd as ta
 from paper_2508_16905_amd import binding as B
 from workloads import get_workload
-from workloads.configs import FP32
 
 pytestmark = pytest.mark.gpu
 

@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2508_16905_amd as ta
 from workloads import get_workload
-from workloads.configs import FP32, TORCH_DTYPE
+from workloads.configs import FP32
 from _gpu_harness import bits_equal, same_or_both_nan
 from _runner import to_numpy
 

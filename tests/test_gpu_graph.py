@@ -2,7 +2,6 @@
 replay is compared with the oracle, with the test's own eager work (copies, synchronisations)
 between the replays."""
 import pytest
-import torch
 
 import paper_2508_16905_amd as ta
 from workloads import get_workload

@@ -7,7 +7,6 @@ term 1e-15 * cond^2 (cond of the supplied products, computed in the test from th
 and norms: 2 ulp(fp32).  The residual is formed from sums on the GPU (G_jj - 2 lambda c + lambda^2
 d), which cancels when the vector has converged: |gpu - oracle| <= 1e-6 * ||Hu|| / ||u||.
 Flags: exact."""
-import ctypes as C
 
 import numpy as np
 import pytest

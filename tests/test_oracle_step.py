@@ -1,7 +1,6 @@
 """Pins for the sequencing of one oracle step (the control loop of Sec. 3.4): skip-step leaves
 every state byte untouched, carry-over without a probe, control interval, and the acceptance
 checks of the synthetic workloads."""
-import copy
 
 import numpy as np
 import pytest

@@ -1,6 +1,5 @@
 """The synthetic parameter sets have the shapes of the paper's two architectures (Sec. 4) and
 the sizes the benchmark configurations name; generators are seeded and reproducible."""
-import numpy as np
 import torch
 
 from workloads import get_workload

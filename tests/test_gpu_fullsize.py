@@ -246,3 +246,24 @@ def test_single_tensor_of_maximum_size():
 def view_of(opt, l, code, a, b):
     """Stored parameters of a slice in their stored dtype (numpy, bit-preserving)."""
     return to_numpy(opt.param(l, code)[a:b]).copy()
+
+
+def test_in_place_resize_through_every_phase():
+    """Storage size changing in place on tensors of 4096 and 4099 chunks (the second one ragged and
+    one phase deeper): every narrowing and widening pair, all phases of the rewrite, every element
+    compared with the oracle.  No probes: only the statistics and the update run."""
+    from _gpu_harness import Pair
+    from test_gpu_parity import custom
+    from workloads.configs import BF16, FP16
+
+    sizes = [4096 * 4096, 4096 * 4096 + 2 * 4096 + 5]
+    for init, target, (lo, hi) in ((FP16, FP32, (0.0, 0.0)), (BF16, FP32, (0.0, 0.0)),
+                                   (FP32, FP16, (1e30, 1e31)), (FP32, BF16, (0.0, 1e30))):
+        wl = custom(sizes, param_dtypes=[init] * len(sizes), tau_low=lo, tau_high=hi, tau_curv=1e30, steps=2)
+        p = Pair(wl)
+        for t in (1, 2):
+            g, z, hz = p.inputs(t, probe=False)
+            p.step(g, z, hz, label=f"{init}->{target} t={t}")
+        assert [(o.prev_code, o.code) for o in p.orc.tensors] == [(target, target)] * 2
+        p.close()
+        print(f"in-place resize {init} -> {target} ok", flush=True)

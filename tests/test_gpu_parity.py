@@ -86,8 +86,8 @@ def test_half_precision_gradients(gd):
 
 def test_every_precision_transition_in_place():
     # initial dtypes x codes forced by the thresholds: each run sends all tensors to one code
-    # up to 64 chunks a tensor is rewritten by one workgroup, beyond that phase by phase: 300007 elements
-    # are 74 chunks (one phase launch), 1100003 are 269 (three)
+    # up to 256 chunks a tensor is rewritten by one workgroup, beyond that phase by phase: 1100003
+    # elements are 269 chunks (one phase launch); the later phases are covered at full size
     sizes = [1, 7, 4096, 4097, 8192, 8193, 20000, 140000, 64 * 4096, 64 * 4096 + 1, 300007, 1100003]
     for target, (lo, hi) in {FP16: (1e30, 1e31), BF16: (0.0, 1e30), FP32: (0.0, 0.0)}.items():
         for init in (FP16, BF16, FP32):

@@ -9,32 +9,43 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "triaccel_oracle.c")
 _SO = os.path.join(_HERE, "liboracle.so")
+_SAN_SO = os.path.join(_HERE, "liboracle_san.so")
 _lib = None
 
 
-def build(force: bool = True) -> str:
+def build(force: bool = True, sanitize: bool = False) -> str:
     """Compile the oracle with gcc.  No contraction, no fast-math; fmaf() maps to the
-    hardware fused multiply-add when the host has one (same result as libm's)."""
-    if not force and os.path.exists(_SO) and os.path.getmtime(_SO) >= os.path.getmtime(_SRC):
-        return _SO
-    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math"]
+    hardware fused multiply-add when the host has one (same result as libm's).
+    ``sanitize``: a second library, ``liboracle_san.so``, instrumented with AddressSanitizer and
+    UndefinedBehaviorSanitizer (every report is fatal); a process loads it instead of the plain one
+    when TRIACCEL_ORACLE_SO names it, and must then have the ASan runtime preloaded."""
+    so = _SAN_SO if sanitize else _SO
+    if not force and os.path.exists(so) and os.path.getmtime(so) >= os.path.getmtime(_SRC):
+        return so
+    cmd = ["gcc", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math"]
+    cmd += ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+        if sanitize else ["-O2"]
     try:
         with open("/proc/cpuinfo") as f:
             if " fma " in f.read():
                 cmd.append("-mfma")
     except OSError:
         pass
-    cmd += ["-o", _SO, _SRC, "-lm"]
+    cmd += ["-o", so, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
-    return _SO
+    return so
 
 
 def lib() -> C.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    build(force=False)
-    L = C.CDLL(_SO)
+    override = os.environ.get("TRIACCEL_ORACLE_SO")
+    if override:
+        L = C.CDLL(override)  # an instrumented build of the same source (sanitizer run of the pins)
+    else:
+        build(force=False)
+        L = C.CDLL(_SO)
     vp, i64, i32, u32, f32, f64 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint32, C.c_float, C.c_double
     u64 = C.c_uint64
     P = C.POINTER

@@ -119,8 +119,9 @@ def test_mixed_state_full_size_sampled_tensors_with_overflow():
     assert wl.total_params == 352321536
     inj7, inj14 = wl.injected_tensor(7), wl.injected_tensor(14)
     sample = sorted({0, 1, 2, 5, 47, 95, inj7})  # both shapes, all three initial dtypes, one injected tensor
-    skipped, codes = run_sampled(wl, sample=sample, steps=15, dev=torch.device("cuda:0"), check_all_every=5)
-    assert skipped[6] == 1 and skipped[13] == 1
+    assert wl.steps == 50
+    skipped, codes = run_sampled(wl, sample=sample, steps=wl.steps, dev=torch.device("cuda:0"), check_all_every=5)
+    assert all(skipped[t - 1] == 1 for t in range(7, 51, 7))
     assert inj14 not in sample  # the second injection hits a tensor the oracle does not hold
     assert set(codes) == {0, 1, 2}
 

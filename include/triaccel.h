@@ -29,8 +29,13 @@
  * the order of the cases in the precision rule, so "promotion" is +1.
  *
  * Return values: 0 on success, a negative TRIACCEL_E_* code otherwise.  Arguments
- * are validated before anything is enqueued; a call that returns an error has
- * changed no optimizer state.  A skipped step (non-finite gradient) is not an error.
+ * are validated before anything is enqueued: a call that returns an argument error
+ * (any code but TRIACCEL_E_HIP) has changed no optimizer state and does not count as
+ * a step.  TRIACCEL_E_HIP from a call that enqueues work means the HIP runtime failed
+ * part-way through the enqueue: the call does not count as a step and its result cannot
+ * be read, but kernels already enqueued may have changed the tensors, so the handle
+ * should be destroyed.  A skipped step (non-finite gradient) is not an error.
+ * Steps are counted in 64 bits (the flags of a skipped step carry the count as their epoch).
  */
 #ifndef TRIACCEL_H
 #define TRIACCEL_H
@@ -116,7 +121,9 @@ typedef struct {
   float loss_scale;         /* S > 0: gradients and hz arrive multiplied by S                       */
   int32_t batch_size;       /* B(t), input of the batch rule                                        */
   uint64_t mem_used_bytes;  /* MemUsage(t); with mem_total_bytes == 0 the library asks the HIP      */
-  uint64_t mem_total_bytes; /* MemMax       runtime (hipMemGetInfo) for both                        */
+  uint64_t mem_total_bytes; /* MemMax       runtime (hipMemGetInfo) for both: a driver round trip,
+                               so it samples them on the first call and on every 16th call after it
+                               and uses the last sample in between                                  */
   int32_t update_curvature; /* only read with curvature_source == 1: non-zero = this step refreshes the
                                curvature EMA, threshold and mask from its gradient (the "every T
                                iterations" of Sec. 3.2 is the caller's schedule); with curvature_source

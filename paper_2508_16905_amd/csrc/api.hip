@@ -33,6 +33,7 @@ int hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 constexpr int kRing = 4;  // pinned staging buffers for the pointer table
+constexpr uint64_t kMemSampleEvery = 16;  // calls between two hipMemGetInfo samples when the caller passes no figures
 
 bool valid_dtype(int32_t d) { return d == TRIACCEL_FP16 || d == TRIACCEL_BF16 || d == TRIACCEL_FP32; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -63,6 +64,7 @@ struct triaccel_ctx {
   int ring_pos = 0;
   GlobalDev* pinned_res = nullptr;
   uint64_t step_index = 0;
+  uint64_t mem_used_cached = 0, mem_total_cached = 0;  // last hipMemGetInfo sample (0: none yet)
   bool result_valid = false;  // a step has been enqueued since init / set_state
   int32_t next_batch = 0;
   int profiling = 0;  // 0 off, 1 every stage boundary, 2 only the boundaries of the update kernel
@@ -443,13 +445,19 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   // stage (4) of the control loop: batch size from memory usage, on the host
   uint64_t used = args->mem_used_bytes, total = args->mem_total_bytes;
   if (total == 0) {
-    size_t free_b = 0, total_b = 0;
-    TA_HIP(hipMemGetInfo(&free_b, &total_b));
-    total = total_b;
-    used = total_b - free_b;
+    // the runtime's figures cost a driver round trip: they are sampled on the first call and then on
+    // every kMemSampleEvery-th one, and the last sample is used in between
+    if (h->mem_total_cached == 0 || h->step_index % kMemSampleEvery == 0) {
+      size_t free_b = 0, total_b = 0;
+      TA_HIP(hipMemGetInfo(&free_b, &total_b));
+      h->mem_total_cached = total_b;
+      h->mem_used_cached = total_b - free_b;
+    }
+    total = h->mem_total_cached;
+    used = h->mem_used_cached;
   }
   const int32_t next_batch = batch_rule(h->cfg, args->batch_size, used, total);
-  // ---- nothing below can fail on the arguments; state may now change ----
+  // ---- nothing below can fail on the arguments ----
   for (int32_t i = 0; i < n; ++i) {
     const triaccel_tensor& t = tensors[i];
     TensorDesc& d = h->desc[i];
@@ -465,36 +473,39 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   const size_t table_bytes = (size_t)n * sizeof(TensorDesc);
   if (!h->desc_valid || std::memcmp(h->desc.data(), h->desc_sent.data(), table_bytes) != 0) {
     const int slot = h->ring_pos;
-    h->ring_pos = (h->ring_pos + 1) % kRing;
     if (h->staging_used[slot]) TA_HIP(hipEventSynchronize(h->staging_ev[slot]));
     std::memcpy(h->staging[slot], h->desc.data(), table_bytes);
+    h->desc_valid = false;  // until the copy below is known to be enqueued
     TA_HIP(hipMemcpyAsync(h->t.tensors, h->staging[slot], table_bytes, hipMemcpyHostToDevice, h->stream));
     TA_HIP(hipEventRecord(h->staging_ev[slot], h->stream));
+    h->ring_pos = (h->ring_pos + 1) % kRing;
     h->staging_used[slot] = true;
     h->desc_sent = h->desc;
     h->desc_valid = true;
   }
 
-  h->step_index += 1;
-  StepScalars sc;
+  // the call counts, and its result can be read, only once all of its work is enqueued
+  const uint64_t index = h->step_index + 1;
+  StepScalars sc{};
   sc.lr = args->lr;
   sc.loss_scale = args->loss_scale;
   sc.inv_scale = 1.0f / args->loss_scale;
-  sc.step_id = (uint32_t)h->step_index;
+  sc.step_id = index;
   const bool prof = h->profiling != 0;
-  h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = 0;
+  h->ev_step[index % TRIACCEL_PROFILE_RING] = 0;
   if (h->use_graph && !prof) {
     const int rc = replay_step(h, sc, any_probe);
     if (rc) return rc;
   } else {
-    hipEvent_t* ev = prof ? h->ev[h->step_index % TRIACCEL_PROFILE_RING] : nullptr;
+    hipEvent_t* ev = prof ? h->ev[index % TRIACCEL_PROFILE_RING] : nullptr;
     const int rc = enqueue_step(h, StepArg{sc, nullptr}, any_probe, ev, h->profiling);
     if (rc) return rc;
     if (prof) {
-      h->ev_step[h->step_index % TRIACCEL_PROFILE_RING] = h->step_index;
-      h->ev_level[h->step_index % TRIACCEL_PROFILE_RING] = h->profiling;
+      h->ev_step[index % TRIACCEL_PROFILE_RING] = index;
+      h->ev_level[index % TRIACCEL_PROFILE_RING] = h->profiling;
     }
   }
+  h->step_index = index;
   h->next_batch = next_batch;
   h->result_valid = true;
   return TRIACCEL_OK;

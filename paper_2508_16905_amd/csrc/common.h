@@ -52,7 +52,8 @@ struct StepScalars {
   float lr;
   float loss_scale;
   float inv_scale;   // 1.0f / loss_scale, one fp32 division on the host
-  uint32_t step_id;  // 1-based count of triaccel_step calls (wraps after 2^32)
+  uint32_t pad_;
+  uint64_t step_id;  // 1-based count of triaccel_step calls; the epoch of the skip / overflow flags
 };
 
 // How a kernel receives them: by value (ordinary launch), or from device memory when `dev` is set
@@ -85,6 +86,7 @@ struct TensorDesc {
 
 // Per-layer device state.  The leading part mirrors triaccel_layer_info.
 struct LayerDev {
+  uint64_t found_epoch;    // step_id at which a non-finite gradient element was last seen
   // reported
   float mean, var, v, theta;
   uint32_t nnz;
@@ -98,7 +100,6 @@ struct LayerDev {
   // bookkeeping
   uint32_t applied_steps;  // steps that were not skipped
   uint32_t probes_seen;
-  uint32_t found_epoch;    // step_id at which a non-finite gradient element was last seen
   // threshold selection
   uint32_t theta_key;      // |theta| bit pattern (scratch while a step selects, then the result)
   uint32_t theta_key_last; // theta of the previous probed step
@@ -130,7 +131,7 @@ struct LayerDev {
 
 // Small global record (device), copied to pinned host memory at the end of a step.
 struct GlobalDev {
-  uint32_t skip_epoch;     // == step_id when the step must be skipped
+  uint64_t skip_epoch;     // == step_id when the step must be skipped
   int32_t good_steps;      // consecutive applied steps since the last loss-scale change
   uint32_t trans_count[2]; // number of tensors whose storage size changes (double-buffered by step parity)
   uint32_t hist_pending[2];// tensors still in histogram mode this step (same double buffering)
@@ -138,8 +139,8 @@ struct GlobalDev {
   // result record
   int32_t res_skipped;
   float res_next_scale;
-  uint32_t res_step_id;
   uint32_t pad_;
+  uint64_t res_step_id;
 };
 
 struct ChunkRef {

@@ -27,8 +27,8 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
   return v;
 }
 
-__device__ __forceinline__ bool step_skipped(const GlobalDev* glob, uint32_t step_id) {
-  return *reinterpret_cast<const volatile uint32_t*>(&glob->skip_epoch) == step_id;
+__device__ __forceinline__ bool step_skipped(const GlobalDev* glob, uint64_t step_id) {
+  return *reinterpret_cast<const volatile uint64_t*>(&glob->skip_epoch) == step_id;
 }
 
 __device__ __forceinline__ StepScalars step_scalars(const StepArg& sa) { return sa.dev ? *sa.dev : sa.value; }

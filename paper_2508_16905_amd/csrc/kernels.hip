@@ -110,8 +110,8 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
     s_sum[0][wave] = s1;
     s_sum[1][wave] = s2;
     if (bad) {
-      atomicExch(&layers[cr.tensor].found_epoch, sc.step_id);
-      atomicExch(&glob->skip_epoch, sc.step_id);
+      atomicExch(reinterpret_cast<unsigned long long*>(&layers[cr.tensor].found_epoch), (unsigned long long)sc.step_id);
+      atomicExch(reinterpret_cast<unsigned long long*>(&glob->skip_epoch), (unsigned long long)sc.step_id);
     }
   }
   __syncthreads();
@@ -435,7 +435,7 @@ __device__ __forceinline__ uint32_t topk_count(int64_t n, uint32_t s_ppm, uint32
 // hit, or small tensor) or the tensor must fall back to histogram passes.
 // ---------------------------------------------------------------------------------------------
 __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob,
-                             const EmaPartial* __restrict__ ema_partials, uint32_t* counters, uint32_t step_id,
+                             const EmaPartial* __restrict__ ema_partials, uint32_t* counters, uint64_t step_id,
                              uint32_t sparsity_ppm, uint32_t topk_abs, uint32_t (*s_red)[kThreads / kWave]) {
   uint32_t above = 0, zeros = 0, maxkey = 0, nonfin = 0, listed = 0;
   for (uint32_t c = threadIdx.x; c < td.n_chunks; c += kThreads) {
@@ -544,7 +544,7 @@ __device__ void select_begin(uint32_t l, const TensorDesc& td, LayerDev& ls, Glo
 // histogram.  Uniform over the workgroup.
 // ---------------------------------------------------------------------------------------------
 __device__ void select_scan(uint32_t l, const TensorDesc& td, LayerDev& ls, GlobalDev* glob, uint32_t* hist,
-                            uint32_t step_id, uint32_t* s_hist, uint32_t* s_part, uint32_t* s_out, bool from_global) {
+                            uint64_t step_id, uint32_t* s_hist, uint32_t* s_part, uint32_t* s_out, bool from_global) {
   const uint32_t bins = ls.win_bins, lo = ls.win_lo, shift = ls.win_shift;
   uint32_t* gh = hist + (size_t)l * kHistBins;
   uint32_t local = 0;

@@ -290,6 +290,28 @@ int triaccel_power_state(triaccel_handle h, triaccel_power_info *out, int32_t n)
 int triaccel_power_times_get(triaccel_handle h, float *ms);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): one power iteration exactly as triaccel_power_iter performs it, but
+ * without a handle and without any allocation, host or device.  The tables and partial sums its kernels
+ * need live in a fixed array inside the library's device code (about 4.3 MiB per GPU, held from the
+ * first call on that GPU until the process ends), which bounds the size of one call:
+ *   n <= TRIACCEL_STATIC_MAX_TENSORS, 1 <= k <= 8, and sum_i ceil(numel[i] / 4096) <=
+ *   TRIACCEL_STATIC_MAX_CHUNKS (268,435,456 elements); larger calls return TRIACCEL_E_INVALID_ARG
+ *   (text in triaccel_last_error) and do nothing.
+ * vectors (host): n entries, u / hu device pointers as for triaccel_power_iter, 16-byte aligned.
+ * numel (host): n element counts, each in (0, 2^31), stride >= numel[i] and a multiple of 4.
+ * info (DEVICE, caller-owned): n records, written in stream order; lambda_latched is set to 0 (nothing is
+ * latched: there is no optimizer handle).  u is overwritten as by triaccel_power_iter, bit for bit.
+ * Asynchronous on `hip_stream` (NULL = the default stream), on the current device.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or threads) race.
+ * The first call on a GPU looks up the array's address; n = 0 does only that (for use before a capture).
+ */
+#define TRIACCEL_STATIC_MAX_TENSORS 256
+#define TRIACCEL_STATIC_MAX_CHUNKS 65536
+int triaccel_power_iter_static(const triaccel_power_tensor *vectors, const int64_t *numel, int32_t n, int32_t k,
+                               triaccel_power_info *info, void *hip_stream);
+
+/*
  * Utility: convert n fp32 values (device) to `dtype` (device) with the same round-to-nearest-even
  * store the update kernel uses; dtype FP32 copies.  Enqueued on `hip_stream`.  Both pointers
  * 16-byte aligned.

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     triaccel_init,
     triaccel_layer_state,
     triaccel_power_iter,
+    triaccel_power_iter_static,
     triaccel_power_state,
     triaccel_power_times_get,
     triaccel_result,

@@ -157,6 +157,8 @@ EXPORTS = {
     "triaccel_power_iter": (C.c_int, [C.c_void_p, C.POINTER(PowerTensor), C.c_int32, C.c_int32, C.c_int32]),
     "triaccel_power_state": (C.c_int, [C.c_void_p, C.POINTER(PowerInfo), C.c_int32]),
     "triaccel_power_times_get": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
+    "triaccel_power_iter_static": (C.c_int, [C.POINTER(PowerTensor), C.POINTER(C.c_int64), C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p]),
 }
 
 _lib: Optional[C.CDLL] = None
@@ -168,7 +170,7 @@ class TriAccelError(RuntimeError):
         detail = ""
         if _lib is not None:
             detail = _lib.triaccel_strerror(code).decode()
-            if code == -6:
+            if code == -6 or (code == -1 and where == "triaccel_power_iter_static"):
                 detail += " -- " + _lib.triaccel_last_error().decode()
         super().__init__(f"{where} failed with code {code}: {detail}")
 
@@ -267,6 +269,15 @@ def triaccel_power_iter(handle, vectors, k: int, latch: bool) -> None:
     """``vectors`` is a ctypes array ``(PowerTensor * n)`` or a sequence of ``PowerTensor``."""
     arr = vectors if isinstance(vectors, C.Array) else (PowerTensor * len(vectors))(*vectors)
     _check(load_library().triaccel_power_iter(handle, arr, len(arr), k, int(latch)), "triaccel_power_iter")
+
+
+def triaccel_power_iter_static(vectors, numel: Sequence[int], k: int, info_ptr: int, stream: int = 0) -> None:
+    """The power iteration without a handle and without allocations.  ``vectors`` as for
+    ``triaccel_power_iter``; ``info_ptr`` is the device address of ``len(vectors)`` PowerInfo records."""
+    arr = vectors if isinstance(vectors, C.Array) else (PowerTensor * len(vectors))(*vectors)
+    ns = (C.c_int64 * len(arr))(*numel)
+    _check(load_library().triaccel_power_iter_static(arr, ns, len(arr), k, C.c_void_p(info_ptr), C.c_void_p(stream)),
+           "triaccel_power_iter_static")
 
 
 def triaccel_power_state(handle, n: int):

@@ -658,6 +658,43 @@ int triaccel_power_iter(triaccel_handle h, const triaccel_power_tensor* vectors,
   return TRIACCEL_OK;
 }
 
+static_assert(sizeof(PowerInfoOut) == sizeof(triaccel_power_info), "the device record is the public one");
+static_assert(TRIACCEL_STATIC_MAX_TENSORS == kStaticMaxTensors && TRIACCEL_STATIC_MAX_CHUNKS == kStaticMaxChunks,
+              "limits of the header");
+
+int triaccel_power_iter_static(const triaccel_power_tensor* vectors, const int64_t* numel, int32_t n, int32_t k,
+                               triaccel_power_info* info, void* hip_stream) {
+  if (n < 0 || n > kStaticMaxTensors) {
+    g_last_error = "triaccel_power_iter_static: at most 256 tensors per call";
+    return TRIACCEL_E_INVALID_ARG;
+  }
+  if (n == 0) {  // set-up only: look up the fixed array of the current device
+    TA_HIP(power_static_prepare());
+    return TRIACCEL_OK;
+  }
+  if (!vectors || !numel || !info) return TRIACCEL_E_NULL_PTR;
+  if (k < 1 || k > kMaxPowerK) return TRIACCEL_E_INVALID_ARG;
+  StaticTensor ts[kStaticMaxTensors];
+  int64_t chunks = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const triaccel_power_tensor& v = vectors[i];
+    if (!v.u || !v.hu) return TRIACCEL_E_NULL_PTR;
+    if (numel[i] <= 0 || numel[i] >= (int64_t(1) << 31)) return TRIACCEL_E_INVALID_ARG;
+    if (v.stride < numel[i] || (v.stride & 3) != 0) return TRIACCEL_E_INVALID_ARG;
+    if (!aligned16(v.u) || !aligned16(v.hu)) return TRIACCEL_E_ALIGNMENT;
+    chunks += (numel[i] + kChunk - 1) / kChunk;
+    ts[i] = StaticTensor{v.u, v.hu, v.stride, numel[i]};
+  }
+  if (chunks > kStaticMaxChunks) {
+    g_last_error = "triaccel_power_iter_static: the tensors of one call may hold at most 65536 pieces of 4096 "
+                   "elements (268,435,456 elements); split the call";
+    return TRIACCEL_E_INVALID_ARG;
+  }
+  if ((reinterpret_cast<uintptr_t>(info) & 3u) != 0) return TRIACCEL_E_ALIGNMENT;
+  TA_HIP(launch_power_iter_static(ts, n, k, reinterpret_cast<PowerInfoOut*>(info), static_cast<hipStream_t>(hip_stream)));
+  return TRIACCEL_OK;
+}
+
 int triaccel_power_state(triaccel_handle h, triaccel_power_info* out, int32_t n) {
   if (!h) return TRIACCEL_E_NOT_INITIALISED;
   if (!out) return TRIACCEL_E_NULL_PTR;

@@ -55,4 +55,33 @@ struct PowerTables {
 // `ev` (four events) the boundaries of the three kernels are recorded on the stream.
 hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s, hipEvent_t* ev);
 
+// The same iteration without a handle and without any allocation: tables and partial sums live in a
+// fixed device array of this library (one per GPU), rebuilt by a small kernel on every call.
+constexpr int kStaticMaxTensors = 256;      // tensors per call
+constexpr int kStaticMaxChunks = 65536;     // sum over the tensors of ceil(numel / kChunk): 268,435,456 elements
+constexpr int kStaticBatch = 64;            // tensor descriptions handed to the table kernel per launch
+
+struct StaticTensor {
+  float* u;
+  const float* hu;
+  int64_t stride;
+  int64_t numel;
+};
+
+// Exported per-tensor record (layout of triaccel_power_info).
+struct PowerInfoOut {
+  float rayleigh[kMaxPowerK];
+  float resid[kMaxPowerK];
+  float hnorm[kMaxPowerK];
+  uint32_t deficient;
+  float lambda_max;
+  float lambda_latched;
+};
+
+// Looks up (once per device) the address of the fixed array on the current device.
+hipError_t power_static_prepare();
+// `tensors` is a host array of n entries; `info` a device array of n records.  The caller has checked
+// the limits above.  Calls on one GPU share the array: they must not overlap in time.
+hipError_t launch_power_iter_static(const StaticTensor* tensors, int n, int k, PowerInfoOut* info, hipStream_t s);
+
 }  // namespace triaccel

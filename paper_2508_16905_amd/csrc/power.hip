@@ -14,6 +14,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "numerics.h"
 
 namespace triaccel {
@@ -253,7 +255,138 @@ hipError_t launch_k(const PowerTables& t, int latch, hipStream_t s, hipEvent_t* 
   return hipSuccess;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The iteration for callers that cannot allocate: every table and partial sum the kernels above
+// use lives in one fixed device array.  Host code never uses the array's name as an address: the
+// device address is looked up once per GPU (each GPU holds its own copy) and passed to the kernels.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+constexpr size_t kStaticMaxSegs = kStaticMaxChunks / kPowerSeg + kStaticMaxTensors;
+constexpr size_t kOffTensors = 0;
+constexpr size_t kOffDescs = kOffTensors + align256(sizeof(TensorDesc) * kStaticMaxTensors);
+constexpr size_t kOffSegFirst = kOffDescs + align256(sizeof(PowerDesc) * kStaticMaxTensors);
+constexpr size_t kOffChunks = kOffSegFirst + align256(sizeof(uint32_t) * kStaticMaxTensors);
+constexpr size_t kOffSegs = kOffChunks + align256(sizeof(ChunkRef) * kStaticMaxChunks);
+constexpr size_t kOffPartials = kOffSegs + align256(sizeof(SegRef) * kStaticMaxSegs);
+constexpr size_t kOffState = kOffPartials + align256(sizeof(double) * power_partial_len(kMaxPowerK) * kStaticMaxSegs);
+constexpr size_t kScratchBytes = kOffState + align256(sizeof(PowerLayer) * kStaticMaxTensors);
+static_assert(kScratchBytes < (size_t(5) << 20), "the fixed array is meant to stay a few MiB");
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU (null: not looked up yet)
+std::mutex g_scratch_mutex;
+
+struct StaticEntry {
+  float* u;
+  const float* hu;
+  int64_t stride;
+  int64_t numel;
+  uint32_t first_chunk;
+  uint32_t first_seg;
+};
+struct StaticBatchArg {
+  uint32_t first;  // index of the batch's first tensor
+  uint32_t count;
+  StaticEntry e[kStaticBatch];
+};
+static_assert(sizeof(StaticBatchArg) <= 3072, "passed by value as a kernel argument");
+
+// Table kernel: workgroup b writes the tables of tensor first + b (descriptor, chunk and segment lists).
+__global__ __launch_bounds__(kThreads) void k_static_tables(StaticBatchArg a, unsigned char* base) {
+  const StaticEntry en = a.e[blockIdx.x];
+  const uint32_t l = a.first + blockIdx.x;
+  const uint32_t nc = (uint32_t)((en.numel + kChunk - 1) / kChunk);
+  const uint32_t ns = (nc + kPowerSeg - 1) / kPowerSeg;
+  if (threadIdx.x == 0) {
+    TensorDesc td{};
+    td.numel = en.numel;
+    td.first_chunk = en.first_chunk;
+    td.n_chunks = nc;
+    reinterpret_cast<TensorDesc*>(base + kOffTensors)[l] = td;
+    reinterpret_cast<PowerDesc*>(base + kOffDescs)[l] = PowerDesc{en.u, en.hu, en.stride};
+    reinterpret_cast<uint32_t*>(base + kOffSegFirst)[l] = en.first_seg;
+  }
+  ChunkRef* chunks = reinterpret_cast<ChunkRef*>(base + kOffChunks) + en.first_chunk;
+  for (uint32_t c = threadIdx.x; c < nc; c += kThreads) chunks[c] = ChunkRef{l, c};
+  SegRef* segs = reinterpret_cast<SegRef*>(base + kOffSegs) + en.first_seg;
+  for (uint32_t q = threadIdx.x; q < ns; q += kThreads) segs[q] = SegRef{l, q};
+}
+
+__global__ void k_static_export(const PowerLayer* __restrict__ state, PowerInfoOut* __restrict__ out, int n) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= n) return;
+  PowerInfoOut o;
+  for (int j = 0; j < kMaxPowerK; ++j) {
+    o.rayleigh[j] = state[l].rayleigh[j];
+    o.resid[j] = state[l].resid[j];
+    o.hnorm[j] = state[l].hnorm[j];
+  }
+  o.deficient = state[l].deficient;
+  o.lambda_max = state[l].lambda_max;
+  o.lambda_latched = 0.0f;
+  out[l] = o;
+}
+
 }  // namespace
+
+hipError_t power_static_prepare() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev]) return hipSuccess;
+  void* p = nullptr;
+  e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!p) return hipErrorInvalidSymbol;
+  g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  return hipSuccess;
+}
+
+hipError_t launch_power_iter_static(const StaticTensor* tensors, int n, int k, PowerInfoOut* info, hipStream_t s) {
+  hipError_t e = power_static_prepare();
+  if (e != hipSuccess) return e;
+  int dev = -1;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  unsigned char* base = g_scratch_ptr[dev];
+  if (n == 0) return hipSuccess;
+  // tables: the prefix sums are formed here, the lists are written on the device
+  uint32_t chunk_pos = 0, seg_pos = 0;
+  for (int first = 0; first < n; first += kStaticBatch) {
+    StaticBatchArg a{};
+    a.first = (uint32_t)first;
+    a.count = (uint32_t)(n - first < kStaticBatch ? n - first : kStaticBatch);
+    for (uint32_t i = 0; i < a.count; ++i) {
+      const StaticTensor& t = tensors[first + (int)i];
+      const uint32_t nc = (uint32_t)((t.numel + kChunk - 1) / kChunk);
+      a.e[i] = StaticEntry{t.u, t.hu, t.stride, t.numel, chunk_pos, seg_pos};
+      chunk_pos += nc;
+      seg_pos += (nc + kPowerSeg - 1) / kPowerSeg;
+    }
+    hipLaunchKernelGGL(k_static_tables, dim3(a.count), dim3(kThreads), 0, s, a, base);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  PowerTables t{};
+  t.tensors = reinterpret_cast<const TensorDesc*>(base + kOffTensors);
+  t.chunks = reinterpret_cast<const ChunkRef*>(base + kOffChunks);
+  t.layers = nullptr;  // only written when a value is latched into an optimizer handle: never here
+  t.descs = reinterpret_cast<PowerDesc*>(base + kOffDescs);
+  t.segs = reinterpret_cast<SegRef*>(base + kOffSegs);
+  t.seg_first = reinterpret_cast<uint32_t*>(base + kOffSegFirst);
+  t.partials = reinterpret_cast<double*>(base + kOffPartials);
+  t.state = reinterpret_cast<PowerLayer*>(base + kOffState);
+  t.n_tensors = (uint32_t)n;
+  t.total_chunks = chunk_pos;
+  t.total_segs = seg_pos;
+  // every partial sum and every record the kernels read is written earlier in this same call, so
+  // nothing in the array has to start at zero
+  if ((e = launch_power_iter(t, k, 0, s, nullptr)) != hipSuccess) return e;
+  hipLaunchKernelGGL(k_static_export, dim3((n + kWave - 1) / kWave), dim3(kWave), 0, s, t.state, info, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_power_iter(const PowerTables& t, int k, int latch, hipStream_t s, hipEvent_t* ev) {
   switch (k) {

@@ -1,13 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the fused Tri-Accel optimizer step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all-fp32]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all-fp32] [--no-variants]
 
 One "step" is one pass of the whole hot path (gradient statistics, curvature EMA, threshold and
 mask, per-layer assignment, update + cast) over every tensor of the workload, with inputs already
 resident in HBM.  Prints ONE JSON line: whole-step throughput in params/s, the HBM roofline of the
 dominant kernel (update + cast) from HIP-event timings taken inside the timed region, per-stage
-figures, and the CPU oracle timed on a bounded sample of the same workload as a baseline.
+figures, the same set measured in its other regimes (`variants`: every layer FP32, steps without a
+probe, a probe every 200th step, the first steps of a run, every layer changing its storage size at
+every step, the mixed-state set), and the CPU oracle timed on bounded samples as a baseline.
+
+Two byte counts are reported for a step.  `moved`: what the kernels of that step have to move given
+what they did (a threshold settled by its predicted band costs no second pass over the curvature).
+`credited`: the method's traffic with the re-read of |h| that an exact order statistic needs in
+general (4.125 B/param on probed steps) counted whether or not the prediction let the kernels skip
+it.  Fractions of the HBM peak are given for both; `step.frac_of_peak` is the moved one.
 """
 import argparse
 import json
@@ -24,19 +32,20 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
 # HBM bytes one launch of the dominant kernel moved on the default workload, from two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by what the same
-# counters read for the library's plain copy kernel: 2.000 and 1.000; see profiles/).  They belong
+# counters read for the library's plain copy kernel; see the summaries under profiles/).  They belong
 # to the kernel sources with the digest below: when the sources differ, `traffic` is null.
-# the files that define the update kernel
 STEP_SOURCES = ("update.hip", "update_body.h", "device_util.h", "numerics.h")
 POWER_SOURCES = ("power.hip", "power.h", "numerics.h")
 MEASURED_TRAFFIC = {
     # k_update<false>, default run of the large_streaming workload
     "step": {"sources_sha256": "1d24179a83d2f96c1c1e782a979bfaf51cdd8a86bc295c56e0f805b84788eb52", "workload": "large_streaming",
-             "alg_bytes": 18991808512, "fetch_bytes": 11.677e9, "write_bytes": 7.348e9},
+             "alg_bytes": 18991808512, "fetch_bytes": 11.677e9, "write_bytes": 7.348e9,
+             "from": "profiles/fused_step_large_streaming_hbm_counters.md"},
     # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
     "power": {"sources_sha256": "5cbb185eadd41b14669fb62e658695710a4237dcda5f869e3390ed3ea3047578", "workload": "large_streaming",
               "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.48e9},
-              "k_power_gram": {"fetch_bytes": 42.95e9, "write_bytes": 0.01e9}},
+              "k_power_gram": {"fetch_bytes": 42.95e9, "write_bytes": 0.01e9},
+              "from": "profiles/power_iteration_large_streaming_k5.md"},
 }
 
 
@@ -49,12 +58,12 @@ def sources_digest(files):
     return h.hexdigest()
 
 
-def measured_traffic(workload, all_fp32, n_tensors_limit, variant, alg_bytes):
-    """Counter-measured HBM bytes per launch of k_update, or None if they do not apply to this run
-    (another workload or variant, or launches that do other work than those of the counter run,
-    e.g. mask passes of tensors that fell back)."""
+def measured_traffic(workload, plain_run, alg_bytes):
+    """Counter-measured HBM bytes per launch of k_update (taken in a separate rocprofv3 run, not in this
+    one), or None if they do not apply: another workload or variant, launches that do other work than
+    those of the counter run (e.g. mask passes of tensors that fell back), or changed kernel sources."""
     m = MEASURED_TRAFFIC["step"]
-    if workload != m["workload"] or all_fp32 or n_tensors_limit or variant or int(alg_bytes) != m["alg_bytes"]:
+    if workload != m["workload"] or not plain_run or int(alg_bytes) != m["alg_bytes"]:
         return None
     if sources_digest(STEP_SOURCES) != m["sources_sha256"]:
         return None
@@ -68,24 +77,133 @@ def measured_power_traffic(workload, k, kernel, n_tensors_limit):
     return m[kernel]["fetch_bytes"] + m[kernel]["write_bytes"]
 
 
-def algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False, elem=False):
-    """Bytes each stage must move for one step, from the definitions of the stages:
-    statistics read g; the EMA reads z, Hz, h and writes h; the mask pass re-reads h and writes one
-    bit per element; the update reads g, the stored parameter and m, and writes the parameter and m."""
+def step_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, momentum, fisher=False, elem=False):
+    """Bytes of one step per kernel stage, from the definitions of the stages: statistics read g; the EMA
+    reads z, Hz, h and writes h; the mask is one bit per element; the update reads g, the stored parameter
+    and m, and writes the parameter and m.  Returns (moved, credited): `moved` charges every pass over h
+    that the threshold selection of this step made (`sel_passes` per tensor, 0 when the predicted band
+    settled it), `credited` charges exactly one re-read of |h| per probed tensor, made or not."""
     size = lambda c: 4 if c == 2 else 2
-    b = dict(grad_stats=0, curv_ema=0, mask_in_ema=0, mask_fallback=0, update=0, update_resize=0)
+    moved = dict(grad_stats=0.0, curv_ema=0.0, select_refine=0.0, update=0.0, update_resize=0.0)
+    reread_credit = 0.0
     for n, pc, c, extra in zip(numel, prev_codes, codes, sel_passes):
-        b["grad_stats"] += n * grad_size
+        moved["grad_stats"] += n * grad_size
         if probed:
             # Hutchinson source: z, Hz, h read, h written; Fisher source: g, h read, h written
-            b["curv_ema"] += n * ((grad_size + 8) if fisher else 16)
-            # the exact threshold needs |h| once more after the pass that creates it; that re-read is
-            # part of the method's traffic whether or not the prediction lets the kernels skip it
-            b["mask_fallback" if extra else "mask_in_ema"] += n * 4 + n / 8.0
+            moved["curv_ema"] += n * ((grad_size + 8) if fisher else 16)
+            if extra:
+                # histogram passes read h; the last extra pass is the mask pass, which rides in the update kernel
+                moved["select_refine"] += n * 4.0 * (extra - 1)
+                moved["update"] += n * 4.0 + n / 8.0
+            else:
+                moved["curv_ema"] += n / 8.0
+            reread_credit += n * 4.0 + n / 8.0
         # the element-wise form of the step size reads h once more in the update
         upd = n * (grad_size + size(pc) + size(c) + (8 if momentum else 0) + (4 if elem else 0))
-        b["update" if size(pc) == size(c) else "update_resize"] += upd
-    return b
+        moved["update" if size(pc) == size(c) else "update_resize"] += upd
+    base = sum(n * grad_size for n in numel)
+    if probed:
+        base += sum(n * ((grad_size + 8) if fisher else 16) for n in numel)
+    base += sum(n * (grad_size + size(pc) + size(c) + (8 if momentum else 0) + (4 if elem else 0))
+                for n, pc, c in zip(numel, prev_codes, codes))
+    return moved, base + reread_credit
+
+
+def build_sets(wl, R, scale, dev, fisher=False, mult=None):
+    """R input batches resident on the GPU: (gradients, z, Hz) per batch.  Generator steps with injected
+    inf/NaN are left out (a skipped step does no work and would flatter the average)."""
+    L = wl.n_tensors
+    gen_steps = [t for t in range(1, 4 * R + 2) if not (wl.inject_every and t % wl.inject_every == 0)][:R]
+    sets = []
+    for j, t in enumerate(gen_steps):
+        grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
+        if mult is not None:
+            for gten in grads:
+                gten.mul_(mult[j % len(mult)])
+        if fisher:
+            sets.append((grads, None, None))
+            continue
+        pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
+        sets.append((grads, [p[0] for p in pr], [p[1] for p in pr]))
+    return sets
+
+
+class Runner:
+    """One optimizer instance driven over cycled input batches."""
+
+    def __init__(self, wl, hyper, sets, dev, graph=False, own_stream=False):
+        import torch
+
+        import paper_2508_16905_amd as ta
+
+        self.ta, self.torch, self.wl, self.hyper, self.sets, self.dev = ta, torch, wl, hyper, sets, dev
+        L = wl.n_tensors
+        stream = torch.cuda.Stream(device=dev) if (graph or own_stream) else None
+        self.opt = ta.TriAccel(hyper, [wl.init_param(l, device=dev) for l in range(L)], grad_dtype=wl.grad_dtype,
+                               stream=stream)
+        if graph:
+            self.opt.set_graph(True)
+        self.graph = graph
+        self.i = 0
+        self.probes = 0
+        self.scale = float(hyper["loss_scale"])
+        self.lr = float(hyper["lr"])
+        self.numel = [wl.numel(l) for l in range(L)]
+        self.grad_size = 4 if wl.grad_dtype == 2 else 2
+        self.fisher = hyper.get("curvature_source", 0) == 1
+        self.elem = hyper.get("elementwise_scale", 0) == 1
+
+    def one(self, probe=True):
+        # gradients cycle with the steps, probe pairs with the probed steps: a probe after a stretch of
+        # steps without one continues the sequence of samples where the last probe left it
+        g = self.sets[self.i % len(self.sets)][0]
+        self.i += 1
+        z = hz = None
+        if probe:
+            _, z, hz = self.sets[self.probes % len(self.sets)]
+            self.probes += 1
+        self.opt.step(g, z, hz, lr=self.lr, loss_scale=self.scale, batch_size=int(self.hyper["batch_size"]),
+                      mem_used_bytes=8, mem_total_bytes=10, update_curvature=probe)
+
+    def run(self, n, probe=True):
+        for _ in range(n):
+            self.one(probe)
+
+    def timed(self, n, probe=True):
+        """n steps bracketed by device synchronisation; returns ms per step."""
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.run(n, probe)
+        self.torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    def bytes_of_last_step(self, probed):
+        state = self.opt.layer_state()
+        moved, credited = step_bytes(self.numel, self.grad_size, [s.prev_code for s in state], [s.code for s in state],
+                                     [s.sel_passes if probed else 0 for s in state], probed,
+                                     self.hyper["momentum"] != 0.0, fisher=self.fisher, elem=self.elem)
+        return state, moved, credited
+
+    def figures(self, ms, probed):
+        """Throughput and both bandwidth figures of a step that took `ms`, with the bytes of the last step."""
+        N = sum(self.numel)
+        state, moved, credited = self.bytes_of_last_step(probed)
+        mv = sum(moved.values())
+        return {
+            "ms_per_step": ms,
+            "params_per_s": N / (ms / 1e3),
+            "moved_bytes_per_param": mv / N,
+            "GBps": mv / 1e9 / (ms / 1e3),
+            "frac_of_peak": mv / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS,
+            "credited_bytes_per_param": credited / N,
+            "credited_frac_of_peak": credited / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS,
+            "codes": {"fp16": sum(s.code == 0 for s in state), "bf16": sum(s.code == 1 for s in state),
+                      "fp32": sum(s.code == 2 for s in state)},
+            "tensors_needing_extra_passes_over_h_last_step": sum(1 for s in state if probed and s.sel_passes),
+        }
+
+    def close(self):
+        self.opt.close()
 
 
 def main():
@@ -116,6 +234,9 @@ def main():
     ap.add_argument("--input-sets", type=int, default=8, help="distinct pre-generated input batches (cycled)")
     ap.add_argument("--cpu-sample-tensors", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="only the headline measurement (profiler runs); by default the large_streaming run also "
+                         "measures the set in its other regimes, a few steps each, into `variants`")
     ap.add_argument("--tensors", type=int, default=0, help="use only the first N tensors of the workload (tuning runs)")
     ap.add_argument("--mode", choices=["step", "power"], default="step",
                     help="step: the fused optimizer step (default, the headline); power: one power iteration")
@@ -158,30 +279,10 @@ def main():
     if args.mode == "power":
         return bench_power(args, wl, hyper, dev)
     L, N = wl.n_tensors, wl.total_params
-    numel = [wl.numel(l) for l in range(L)]
-    grad_size = 4 if wl.grad_dtype == 2 else 2
     scale = float(hyper["loss_scale"])
-
-    params = [wl.init_param(l, device=dev) for l in range(L)]
-    stream = torch.cuda.Stream(device=dev) if (args.graph or args.own_stream) else None
-    opt = ta.TriAccel(hyper, params, grad_dtype=wl.grad_dtype, stream=stream)
-    del params
     R = max(1, min(args.input_sets, K + max(W, args.settle)))
-    sets = []
-    # generator steps to draw the input batches from (steps with injected inf/NaN are left out:
-    # a skipped step does no work and would flatter the average)
-    gen_steps = [t for t in range(1, 4 * R + 2) if not (wl.inject_every and t % wl.inject_every == 0)][:R]
-    for j, t in enumerate(gen_steps):
-        grads = [wl.grad(t, l, scale, device=dev) for l in range(L)]
-        if args.switch_stress:
-            # unscaled standard deviation 0.0316 x {0.3, 3, 30}: variance below tau_low, between, above tau_high
-            for gten in grads:
-                gten.mul_((0.3, 3.0, 30.0)[j % 3])
-        if args.fisher:
-            sets.append((grads, None, None))
-            continue
-        pr = [wl.probe(t, l, scale, device=dev) for l in range(L)]
-        sets.append((grads, [p[0] for p in pr], [p[1] for p in pr]))
+    # unscaled standard deviation 0.0316 x {0.3, 3, 30}: variance below tau_low, between, above tau_high
+    sets = build_sets(wl, R, scale, dev, fisher=args.fisher, mult=SWITCH_MULT if args.switch_stress else None)
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {L} tensors, {N} params, {R} input sets resident, "
           f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated", file=sys.stderr, flush=True)
@@ -196,39 +297,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    run = Runner(wl, hyper, sets, dev, graph=args.graph, own_stream=args.own_stream)
+    opt = run.opt
     # In the timed region only the dominant kernel (update + cast) is bracketed by HIP events: every
     # recorded event costs the stream a few microseconds.  A graph replay carries no events at all.
-    if args.graph:
-        opt.set_graph(True)
-    else:
+    if not args.graph:
         opt.set_profiling(1 if args.switch_stress else 2)
-    lr = float(hyper["lr"])
-
-    def one(i, probe=True):
-        g, z, hz = sets[i % R]
-        if not probe:
-            z = hz = None
-        opt.step(g, z, hz, lr=lr, loss_scale=scale, batch_size=int(hyper["batch_size"]),
-                 mem_used_bytes=8, mem_total_bytes=10, update_curvature=probe)
 
     # bring the run to its steady state first when the warm-up alone is shorter than that takes
     P = max(0, args.settle - W)
-    for i in range(P):
-        one(i)
-    for i in range(P, P + W):
-        one(i)
+    run.run(P + W)
     if P + W > 0:
         res = opt.result()
         assert not res.skipped
     codes_before = [s.code for s in opt.layer_state()]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
     probed = not args.no_probe
-    for i in range(P + W, P + W + K):
-        one(i, probed)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
+    ms_per_step = run.timed(K, probed)
     res = opt.result()
     assert not res.skipped and res.step_index == P + W + K
     KP = min(K, 63)  # the library keeps the event times of the last 64 steps
@@ -237,25 +321,17 @@ def main():
     # stage breakdown: the same number of steps again, launched kernel by kernel with an event at
     # every stage boundary (not part of the timed region)
     opt.set_profiling(1)
-    for i in range(P + W + K, P + W + K + KP):
-        one(i, probed)
+    run.run(KP, probed)
     opt.result()
-    state = opt.layer_state()
-    codes = [s.code for s in state]
-    prev_codes = [s.prev_code for s in state]
     stage_ms = [opt.stage_times(back) for back in range(KP)]
     mean_ms = {name: sum(s[i] for s in stage_ms) / KP for i, name in enumerate(ta.STAGE_NAMES)}
 
-    # algorithmic traffic of the last timed step (codes are stationary over the timed region
-    # unless a layer switched; the count of switches is reported)
+    # traffic of the last step (codes are stationary over the timed region unless a layer switched;
+    # the count of switches is reported)
+    fig = run.figures(ms_per_step, probed)
+    state, moved, credited = run.bytes_of_last_step(probed)
+    codes = [s.code for s in state]
     switched = sum(1 for a, b in zip(codes_before, codes) if a != b)
-    sel_passes = [s.sel_passes for s in state]
-    alg = algorithmic_bytes(numel, grad_size, prev_codes, codes, sel_passes, probed, hyper["momentum"] != 0.0,
-                            fisher=args.fisher, elem=args.elementwise)
-    total_bytes = sum(alg.values())
-    # bytes each kernel stage actually has to move in the last timed step
-    moved = {"grad_stats": alg["grad_stats"], "curv_ema": alg["curv_ema"] + alg["mask_in_ema"] / 33.0,
-             "update": alg["update"] + alg["mask_fallback"], "update_resize": alg["update_resize"]}
     stages = {}
     for name in ta.STAGE_NAMES:
         entry = {"ms": round(mean_ms[name], 4)}
@@ -266,6 +342,7 @@ def main():
     upd_ms = mean_ms["update"] if upd_ms_timed is None else upd_ms_timed
     upd_gbps = moved["update"] / 1e9 / (upd_ms / 1e3)
     dominant, dominant_bytes = "k_update (fused update + cast)", moved["update"]
+    grad_size = run.grad_size
     if args.switch_stress:
         # every step of the cycle sends all tensors through one of the two kernels; report the in-place
         # resize with its bytes and time averaged over the steps of the timed region
@@ -274,7 +351,8 @@ def main():
         # two of the three steps of the cycle change the size: 2 -> 4 bytes and 4 -> 2 bytes per parameter
         dominant_bytes = (2.0 / 3.0) * N * (grad_size + 6 + (8 if hyper["momentum"] != 0.0 else 0))
         upd_gbps = dominant_bytes / 1e9 / (upd_ms / 1e3)
-    step_gbps = total_bytes / 1e9 / (ms_per_step / 1e3)
+    plain_run = not (args.all_fp32 or args.tensors or args.fisher or args.elementwise or args.switch_stress)
+    traffic = measured_traffic(wl.name, plain_run, dominant_bytes)
 
     out = {
         "metric": "fused Tri-Accel step params/sec and achieved HBM GB/s (% of peak), 1 GPU",
@@ -296,9 +374,9 @@ def main():
             "all_fp32": bool(args.all_fp32),
             "step_size": "per element" if args.elementwise else "per layer",
             "curvature_source": "empirical Fisher (squared gradient)" if args.fisher else "Hutchinson pair (z, Hz)",
-            "codes": {"fp16": codes.count(0), "bf16": codes.count(1), "fp32": codes.count(2)},
+            "codes": fig["codes"],
             "layers_switched_in_timed_region": switched,
-            "tensors_needing_extra_passes_over_h_last_step": sum(1 for x in sel_passes if x),
+            "tensors_needing_extra_passes_over_h_last_step": fig["tensors_needing_extra_passes_over_h_last_step"],
             "input_sets": R,
             "settle_steps_before_warmup": P,
             "launch": "HIP graph replay" if args.graph else "kernel by kernel",
@@ -315,14 +393,21 @@ def main():
             "unit": "GB/s",
             "frac": upd_gbps / HBM_PEAK_GBPS,
             "alg_bytes_per_launch": dominant_bytes,
-            "traffic": measured_traffic(wl.name, args.all_fp32, args.tensors, args.fisher or args.elementwise or args.switch_stress,
-                                        dominant_bytes),
+            "traffic": traffic,
+            "traffic_from": None if traffic is None else
+                            "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, summarised in "
+                            + MEASURED_TRAFFIC["step"]["from"] + " (not counters of this run)",
         },
         "step": {
-            "alg_bytes_per_param": total_bytes / N,
-            "alg_GB": total_bytes / 1e9,
-            "GBps": step_gbps,
-            "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
+            # bytes the kernels of the step had to move, and the same with the re-read of |h| credited
+            "moved_bytes_per_param": fig["moved_bytes_per_param"],
+            "moved_GB": fig["moved_bytes_per_param"] * N / 1e9,
+            "GBps": fig["GBps"],
+            "frac_of_peak": fig["frac_of_peak"],
+            "credited_bytes_per_param": fig["credited_bytes_per_param"],
+            "credited_GB": credited / 1e9,
+            "credited_GBps": credited / 1e9 / (ms_per_step / 1e3),
+            "credited_frac_of_peak": fig["credited_frac_of_peak"],
             # HIP-event time from the first to the last kernel of a step, median over the steps of
             # the stage breakdown (an event at every stage boundary costs the stream a few microseconds)
             "ms_events_median": sorted(sum(s) for s in stage_ms)[KP // 2],
@@ -330,10 +415,124 @@ def main():
         "stages": stages,
     }
 
+    want_variants = (not args.no_variants and plain_run and wl.name == "large_streaming" and not args.graph
+                     and not args.no_probe and len(sets) >= 6)
+    if want_variants:
+        out["variants"] = variants(run, wl, hyper, sets, dev, min(K, 10))
+    else:
+        run.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, hyper, sets[0], args.cpu_sample_tensors, scale)
-    opt.close()
+        out["cpu_baseline"] = cpu_baseline(wl, hyper, args.cpu_sample_tensors, scale)
+        if want_variants:
+            out["cpu_baseline"]["per_config"] = cpu_per_config()
     print(json.dumps(out))
+
+
+SWITCH_MULT = (0.3, 3.0, 30.0)
+
+
+def variants(run, wl, hyper, sets, dev, K):
+    """The same parameter set in its other regimes, K timed steps each (same process, same resident
+    inputs); the mixed-state set last, on inputs of its own.  `run` is the headline's runner in steady
+    state; it is closed here."""
+    import torch
+
+    from workloads import get_workload
+
+    N = wl.total_params
+    v = {}
+    # (1) the ordinary step between two curvature refreshes
+    run.opt.set_profiling(2)
+    run.run(3, probe=False)
+    ms = run.timed(K, probe=False)
+    v["no_probe"] = run.figures(ms, probed=False)
+    v["no_probe"]["k_update_ms"] = sum(run.opt.stage_times(b)[4] for b in range(K)) / K
+
+    # (2) the paper's refresh schedule (Sec. 4.1: T = 200): two periods, a probe on the first step of each
+    outcomes = {}
+    extra = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for period in range(2):
+        run.one(probe=True)
+        for s in run.opt.layer_state():       # synchronises: two of the 400 steps pay for it
+            outcomes[int(s.sel_outcome)] = outcomes.get(int(s.sel_outcome), 0) + 1
+            extra += int(s.sel_passes)
+        run.run(199, probe=False)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / 400
+    v["probe_every_200"] = {
+        "ms_per_step": ms, "params_per_s": N / (ms / 1e3), "steps": 400, "probe_steps": 2,
+        "band_check_outcomes_over_probe_steps_x_tensors": {str(k): n for k, n in sorted(outcomes.items())},
+        "extra_passes_over_h": extra,
+        "note": "outcome 1 = the predicted band settled the threshold in the EMA pass; the predictor only sees "
+                "probed steps, so its state after P probes is the same whatever the spacing of the probes",
+    }
+    run.close()
+
+    # (3) every layer stored in FP32: the 44.125 B/param case (the worked example prints 40.125)
+    r = Runner(wl, dict(hyper, tau_low=0.0, tau_high=0.0), sets, dev)
+    r.opt.set_profiling(2)
+    r.run(64)
+    ms = r.timed(K)
+    f = r.figures(ms, True)
+    f["k_update_ms"] = sum(r.opt.stage_times(b)[4] for b in range(K)) / K
+    f["frac_of_peak_at_40.125_bytes_per_param"] = 40.125 * N / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS
+    v["all_fp32"] = f
+    r.close()
+
+    # (4) the first steps of a run: no threshold prediction yet, every tensor goes through the fallback
+    r = Runner(wl, hyper, sets, dev)
+    first = []
+    for t in range(1, 7):
+        ms = r.timed(1)
+        st = r.opt.layer_state()
+        first.append({"step": t, "ms": ms, "tensors_with_extra_passes": sum(1 for s in st if s.sel_passes),
+                      "extra_passes_over_h": sum(int(s.sel_passes) for s in st)})
+    v["first_steps"] = first
+    r.close()
+
+    # (5) every layer changes its storage size at (two of three) steps: the in-place resize
+    for j, (grads, _, _) in enumerate(sets[:6]):
+        for g in grads:
+            g.mul_(SWITCH_MULT[j % 3])
+    r = Runner(wl, dict(hyper, beta_var=0.0, tau_curv=1e30), sets[:6], dev)
+    r.opt.set_profiling(1)
+    r.run(60)
+    K3 = max(3, (K // 3) * 3)
+    ms = r.timed(K3)
+    resize_ms = sum(r.opt.stage_times(b)[5] for b in range(K3)) / K3
+    update_ms = sum(r.opt.stage_times(b)[4] for b in range(K3)) / K3
+    gs = r.grad_size
+    resize_bytes = (2.0 / 3.0) * N * (gs + 6 + (8 if hyper["momentum"] != 0.0 else 0))
+    # bytes of an average step of the cycle: statistics, EMA + mask, and the update at 2->2, 2->4, 4->2 bytes
+    avg_bytes = N * (gs + 16.125) + N * (gs + 8) + N * (4 + 6 + 6) / 3.0
+    v["switch_stress"] = {
+        "ms_per_step": ms, "params_per_s": N / (ms / 1e3),
+        "moved_bytes_per_param": avg_bytes / N, "GBps": avg_bytes / 1e9 / (ms / 1e3),
+        "frac_of_peak": avg_bytes / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS,
+        "k_update_resize_ms_avg": resize_ms, "k_update_ms_avg": update_ms,
+        "k_update_resize_GBps": resize_bytes / 1e9 / (resize_ms / 1e3),
+        "k_update_resize_frac_of_peak": resize_bytes / 1e9 / (resize_ms / 1e3) / HBM_PEAK_GBPS,
+        "note": "an event at every stage boundary in the timed steps (the resize is several launches)",
+    }
+    r.close()
+    del r
+    sets.clear()
+    torch.cuda.empty_cache()
+
+    # (6) the mixed-state set: fp16 gradients, three storage formats
+    wm = get_workload("mixed_state")
+    hm = dict(wm.hyper)
+    sm = build_sets(wm, 8, float(hm["loss_scale"]), dev)
+    r = Runner(wm, hm, sm, dev)
+    r.opt.set_profiling(2)
+    r.run(64)
+    ms = r.timed(max(K, 20))
+    v["mixed_state"] = r.figures(ms, True)
+    v["mixed_state"]["workload"] = f"{wm.n_tensors} tensors, {wm.total_params} params, fp16 gradients"
+    r.close()
+    return v
 
 
 def bench_power(args, wl, hyper, dev):
@@ -377,6 +576,7 @@ def bench_power(args, wl, hyper, dev):
     pass_bytes = 8.0 * k * N   # each pass: k vectors read + k vectors read or written, 4 bytes each
     gram_gbps, apply_gbps = pass_bytes / 1e9 / (stage[0] / 1e3), pass_bytes / 1e9 / (stage[2] / 1e3)
     dom = ("k_power_gram", stage[0], gram_gbps) if stage[0] >= stage[2] else ("k_power_apply", stage[2], apply_gbps)
+    traffic = measured_power_traffic(wl.name, k, dom[0], args.tensors)
     out = {
         "metric": "power-iteration throughput (params/s per iteration on k vectors per layer)",
         "value": N / (ms / 1e3), "unit": "params/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
@@ -384,7 +584,8 @@ def bench_power(args, wl, hyper, dev):
         "config": {"workload": f"{wl.name}: {L} tensors, {N} params, one power iteration on k = {k} fp32 vectors per tensor"},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": dom[2], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dom[2] / HBM_PEAK_GBPS, "alg_bytes_per_launch": pass_bytes,
-                     "traffic": measured_power_traffic(wl.name, k, dom[0], args.tensors)},
+                     "traffic": traffic,
+                     "traffic_from": None if traffic is None else MEASURED_TRAFFIC["power"]["from"] + " (not counters of this run)"},
         "step": {"alg_bytes_per_param": 16.0 * k, "alg_GB": 2 * pass_bytes / 1e9,
                  "GBps": 2 * pass_bytes / 1e9 / (ms / 1e3), "frac_of_peak": 2 * pass_bytes / 1e9 / (ms / 1e3) / HBM_PEAK_GBPS},
         "stages": {"gram": {"ms": round(stage[0], 4), "GBps": round(gram_gbps, 1)}, "layer": {"ms": round(stage[1], 4)},
@@ -410,7 +611,17 @@ def bench_power(args, wl, hyper, dev):
     print(json.dumps(out))
 
 
-def cpu_baseline(wl, hyper, first_set, n_sample, scale):
+def _oracle_timed(orc, gs, zs, hzs, args, budget_s):
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        orc.step(gs, zs, hzs, *args)
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or steps >= 2000:
+            return steps, dt
+
+
+def cpu_baseline(wl, hyper, n_sample, scale):
     """The CPU oracle, as it stands, timed on a bounded sample of the same workload: the first tensors
     up to about 1.5e8 parameters (the whole workload when it is smaller), as many steps as fit in
     about six seconds of wall time (twice: all cores, then one thread)."""
@@ -423,27 +634,22 @@ def cpu_baseline(wl, hyper, first_set, n_sample, scale):
     cores = max(1, min(len(idx), 16, os.cpu_count() or 1))
     cfg = oracle.OracleConfig.from_hyper(hyper)
     params = [to_numpy(wl.init_param(l)) for l in idx]
-    g = [to_numpy(first_set[0][l]) for l in idx]
-    z = [None if first_set[1] is None else to_numpy(first_set[1][l]) for l in idx]
-    hz = [None if first_set[2] is None else to_numpy(first_set[2][l]) for l in idx]
+    # inputs of the first generator step, drawn again (the resident batches may have been released)
+    dev = "cuda:0"
+    g = [to_numpy(wl.grad(1, l, scale, device=dev)) for l in idx]
+    if hyper.get("curvature_source", 0) == 1:
+        z = hz = [None] * len(idx)
+    else:
+        pr = [wl.probe(1, l, scale, device=dev) for l in idx]
+        z, hz = [to_numpy(p[0]) for p in pr], [to_numpy(p[1]) for p in pr]
     args = (float(hyper["lr"]), scale, int(hyper["batch_size"]), 8, 10)
-
-    def timed(orc, gs, zs, hzs):
-        steps, t0 = 0, time.perf_counter()
-        while True:
-            orc.step(gs, zs, hzs, *args)
-            steps += 1
-            dt = time.perf_counter() - t0
-            if dt >= 6.0 or steps >= 2000:
-                return steps, dt
-
     orc = oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx), workers=cores)
-    steps, dt = timed(orc, g, z, hz)
+    steps, dt = _oracle_timed(orc, g, z, hz, args, 6.0)
     n = sum(wl.numel(l) for l in idx)
     # the same oracle on one thread, largest tensor of the sample only
     big = max(range(len(idx)), key=lambda i: wl.numel(idx[i]))
     one = oracle.OracleTriAccel(cfg, [params[big]], [wl.init_dtype(idx[big])], [wl.grad_dtype], workers=1)
-    steps1, dt1 = timed(one, [g[big]], [z[big]], [hz[big]])
+    steps1, dt1 = _oracle_timed(one, [g[big]], [z[big]], [hz[big]], args, 6.0)
     return {
         "value": n * steps / dt,
         "unit": "params/s",
@@ -453,6 +659,34 @@ def cpu_baseline(wl, hyper, first_set, n_sample, scale):
         "single_thread_value": wl.numel(idx[big]) * steps1 / dt1,
         "single_thread_sample": f"one tensor ({wl.numel(idx[big])} params), {steps1} step(s), {dt1:.2f} s wall",
     }
+
+
+def cpu_per_config():
+    """The oracle on the other four configurations, about two seconds each, all cores (the largest of them
+    on its first tensors up to about 2e7 parameters)."""
+    import oracle
+    from _runner import to_numpy
+    from workloads import get_workload
+
+    out = {}
+    for name in ("tiny_mlp", "resnet18", "efficientnet_b0", "mixed_state"):
+        wl = get_workload(name)
+        idx = list(range(wl.n_tensors))
+        while len(idx) > 1 and sum(wl.numel(l) for l in idx) > 20_000_000:
+            idx.pop()
+        scale = float(wl.hyper["loss_scale"])
+        cores = max(1, min(len(idx), 16, os.cpu_count() or 1))
+        cfg = oracle.OracleConfig.from_hyper(wl.hyper)
+        params = [to_numpy(wl.init_param(l)) for l in idx]
+        g = [to_numpy(wl.grad(1, l, scale)) for l in idx]
+        pr = [wl.probe(1, l, scale) for l in idx]
+        z, hz = [to_numpy(p[0]) for p in pr], [to_numpy(p[1]) for p in pr]
+        orc = oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx), workers=cores)
+        steps, dt = _oracle_timed(orc, g, z, hz, (float(wl.hyper["lr"]), scale, int(wl.hyper["batch_size"]), 8, 10), 2.0)
+        n = sum(wl.numel(l) for l in idx)
+        out[name] = {"value": n * steps / dt, "unit": "params/s", "cores": cores,
+                     "sample": f"{len(idx)} of {wl.n_tensors} tensors ({n} params), {steps} step(s), {dt:.2f} s wall"}
+    return out
 
 
 if __name__ == "__main__":

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restric
   const TensorDesc td = tds[cr.tensor];
   const int64_t base = (int64_t)cr.index * kChunk;
   const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
-  if (elem_size(pd) == elem_size(nd)) update_any<ELEM>(td, pd, nd, base, sc.inv_scale, wd, mu, ss, false, (int)threadIdx.x);
+  if (elem_size(pd) == elem_size(nd)) update_any<ELEM>(td, pd, nd, base, sc.inv_scale, wd, mu, ss, (int)threadIdx.x);
   if constexpr (ELEM) return;
   // kSelHist cannot remain after the last scan; never write a mask from a stale range
   const uint32_t mode = ls.mode;

@@ -1,73 +1,56 @@
 // gfx950 kernels: in-place update of tensors whose storage size changes (2 <-> 4 bytes per element),
 // and the stand-alone conversion utility.
+#include "resize_schedule.h"
 #include "update_body.h"
 
 namespace triaccel {
 
-// Tensors whose storage size changes (2 <-> 4 bytes per element) are rewritten in place in
-// phases: phase 0 is chunk 0, phase p >= 1 the chunks [2^(p-1), 2^p).  Inside a phase the bytes
-// written (element range [lo, hi) at the new size) never overlap the bytes read (same range at
-// the old size) because hi <= 2 lo.  Narrowing runs the phases in ascending order, so every
-// write lands on bytes whose old contents were consumed by an earlier phase; widening runs them
-// in descending order for the same reason.
+// Tensors whose storage size changes (2 <-> 4 bytes per element) are rewritten in place, in the
+// order resize_schedule.h lays down: stage 0 (the first chunks of a tensor, one workgroup, a barrier
+// between the loads and the stores of every chunk), then subtree stages in which every workgroup
+// walks the levels of its own subtree of chunks with a barrier between levels.  No workgroup waits
+// for another; what a stage depends on was done by an earlier launch.  Launch q performs stage q for
+// the narrowing tensors of the step's list and stage n_stages - 1 - q for the widening ones.
 //
-// The phases up to kSerialPhase (the first kSerialChunks chunks) are done by ONE workgroup per
-// tensor in a single launch: a workgroup of 1024 threads takes four consecutive chunks per
-// iteration (every 256-thread part loads its chunk, the workgroup synchronises, then stores), in
-// ascending order when narrowing and in descending order when widening; what such a group of four
-// overwrites was read by an earlier iteration, or by the same one before its barrier.  Each later
-// phase is a launch of its own.  With L = the last phase of the largest tensor there are
-// n_launch = 1 + max(0, L - kSerialPhase) launches:
-//   narrowing:  launch 0 = serial part, launch j >= 1 = phase kSerialPhase + j;
-//   widening:   launch j < n_launch - 1 = phase L - j, launch n_launch - 1 = serial part.
-// A tensor with fewer phases than the largest one skips the launches beyond its own.  The first
-// and the last launch run with 1024 threads per workgroup (their phase work is then spread over
-// the four parts of a workgroup), the others with 256.
-constexpr uint32_t kSerialPhase = 8;
-constexpr uint32_t kSerialChunks = 1u << kSerialPhase;  // 256 chunks = 1,048,576 elements
-constexpr int kSerialParts = 4;                          // 256-thread parts of the serial workgroup
-
+// Work items of a launch are (list entry, workgroup of that tensor) pairs, `slots` per entry (the
+// larger of the two stages' workgroup counts); a workgroup takes the items blockIdx.x,
+// blockIdx.x + gridDim.x, ...  The list and its length are written on the device by the per-layer
+// kernel, so every launch is made on every step and leaves at once when the list is empty.
 template <bool ELEM>
-__global__ __launch_bounds__(kSerialParts * kThreads) void k_update_resize(
-    const TensorDesc* __restrict__ tds, const LayerDev* layers, const GlobalDev* glob, const uint32_t* trans_list,
-    uint32_t n_tensors, uint32_t launch, uint32_t n_launch, StepArg sa, float wd, float mu, float alpha) {
+__global__ __launch_bounds__(kThreads) void k_update_resize(const TensorDesc* __restrict__ tds, const LayerDev* layers,
+                                                            const GlobalDev* glob, const uint32_t* trans_list,
+                                                            uint32_t n_tensors, ResizePlan plan, uint32_t launch,
+                                                            uint32_t slots, StepArg sa, float wd, float mu, float alpha) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
   const uint32_t count = glob->trans_count[sc.step_id & 1u];
   const uint32_t* list = trans_list + (sc.step_id & 1u) * n_tensors;
-  const uint32_t parts = blockDim.x / kThreads;  // 1 or kSerialParts
-  const uint32_t part = threadIdx.x / kThreads;
-  const int lane = (int)(threadIdx.x % kThreads);
-  for (uint32_t i = 0; i < count; ++i) {
-    const uint32_t l = list[i];
-    const TensorDesc td = tds[l];
+  const int tid = (int)threadIdx.x;
+  const uint64_t items = (uint64_t)count * slots;
+  for (uint64_t item = blockIdx.x; item < items; item += gridDim.x) {
+    const uint32_t l = list[item / slots];
+    const uint32_t r = (uint32_t)(item % slots);
     const LayerDev& ls = layers[l];
     const int pd = ls.prev_code, nd = ls.code;
     const bool narrowing = elem_size(nd) < elem_size(pd);
+    const uint32_t stage = resize_stage_of_launch(plan, launch, narrowing);
+    if (r >= resize_stage_roots(plan, stage)) continue;
+    const TensorDesc td = tds[l];
     const StepSize ss{-ls.eta, sc.lr, alpha, ls.theta_key};
-    const bool serial = narrowing ? launch == 0 : launch == n_launch - 1u;
-    if (serial) {
-      if (i % gridDim.x != blockIdx.x) continue;  // one workgroup per tensor
-      const uint32_t n_ser = min(kSerialChunks, td.n_chunks);
-      const uint32_t n_it = (n_ser + parts - 1u) / parts;
-      for (uint32_t it = 0; it < n_it; ++it) {
-        const uint32_t c = (narrowing ? it : n_it - 1u - it) * parts + part;
-        // every thread of the workgroup meets exactly one barrier per iteration
-        if (c < n_ser) update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, true, lane);
-        else __syncthreads();
-      }
-      continue;
+    if (stage == 0) {
+      resize_walk_top(plan, td.n_chunks, narrowing, [&](uint32_t c) {
+        ChunkRegs regs;
+        update_load_any<ELEM>(td, pd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, tid, regs);
+        __syncthreads();  // chunk 0 overwrites itself; a later chunk overwrites what an earlier one loaded
+        update_store_any(td, nd, (int64_t)c * kChunk, tid, regs);
+      });
+    } else {
+      if (plan.root[stage] + r >= td.n_chunks) continue;
+      resize_walk_subtree(
+          plan, stage, r, td.n_chunks, narrowing,
+          [&](uint32_t c) { update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, tid); },
+          [&]() { __syncthreads(); });
     }
-    // number of phases: 1 + ceil(log2(n_chunks))
-    const uint32_t last_phase = td.n_chunks <= 1 ? 0u : 32u - (uint32_t)__clz(td.n_chunks - 1u);
-    const uint32_t phase = narrowing ? kSerialPhase + launch : kSerialPhase + (n_launch - 1u - launch);
-    if (phase > last_phase) continue;
-    const uint32_t c_lo = 1u << (phase - 1u);  // phase > kSerialPhase >= 1
-    const uint32_t c_hi = min(1u << phase, td.n_chunks);
-    // a chunk c >= 1 reads and writes disjoint bytes (its element range at the old and at the new
-    // size do not meet), so these phases need no synchronisation between its loads and its stores
-    for (uint32_t c = c_lo + blockIdx.x * parts + part; c < c_hi; c += gridDim.x * parts)
-      update_any<ELEM>(td, pd, nd, (int64_t)c * kChunk, sc.inv_scale, wd, mu, ss, false, lane);
   }
 }
 
@@ -98,22 +81,19 @@ __global__ __launch_bounds__(kThreads) void k_cast(const float* __restrict__ src
 
 hipError_t launch_update_resize(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha,
                                 bool elem, hipStream_t s) {
-  // last phase of the largest tensor: ceil(log2(chunks)); a phase holds at most half the chunks of a tensor
-  uint32_t last_phase = 0;
-  while ((1u << last_phase) < t.max_chunks_per_tensor) ++last_phase;
-  const uint32_t n_launch = 1u + (last_phase > kSerialPhase ? last_phase - kSerialPhase : 0u);
-  uint32_t grid = (t.max_chunks_per_tensor + 1) / 2;
-  if (grid < 1) grid = 1;
-  if (grid > t.persistent_grid) grid = t.persistent_grid;
-  for (uint32_t launch = 0; launch < n_launch; ++launch) {
-    // the launches that hold a serial part use the wide workgroup
-    const uint32_t threads = (launch == 0 || launch == n_launch - 1u) ? kSerialParts * kThreads : kThreads;
+  const ResizePlan plan = make_resize_plan(t.max_chunks_per_tensor, t.total_chunks);
+  for (uint32_t launch = 0; launch < plan.n_stages; ++launch) {
+    // a narrowing tensor is at stage `launch`, a widening one at the mirrored stage
+    const uint32_t a = resize_stage_roots(plan, launch), b = resize_stage_roots(plan, plan.n_stages - 1u - launch);
+    const uint32_t slots = a > b ? a : b;
+    uint64_t grid = (uint64_t)t.n_tensors * slots;
+    if (grid > 65536u) grid = 65536u;
     if (elem)
-      hipLaunchKernelGGL(k_update_resize<true>, dim3(grid), dim3(threads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
+      hipLaunchKernelGGL(k_update_resize<true>, dim3((uint32_t)grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, plan, launch, slots, sa, wd, mu, alpha);
     else
-      hipLaunchKernelGGL(k_update_resize<false>, dim3(grid), dim3(threads), 0, s, t.tensors, t.layers, t.glob,
-                         t.trans_list, t.n_tensors, launch, n_launch, sa, wd, mu, alpha);
+      hipLaunchKernelGGL(k_update_resize<false>, dim3((uint32_t)grid), dim3(kThreads), 0, s, t.tensors, t.layers, t.glob,
+                         t.trans_list, t.n_tensors, plan, launch, slots, sa, wd, mu, alpha);
     TA_LAUNCH_CHECK();
   }
   return hipSuccess;

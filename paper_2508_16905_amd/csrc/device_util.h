@@ -58,7 +58,7 @@ __device__ __forceinline__ void store_mask_words(const TensorDesc& td, int64_t b
 #pragma unroll
     for (int r = 1; r < kRows; ++r) v = (sub == r) ? word[r] : v;
     const int64_t widx = ((base + (int64_t)sub * kRowElems) >> 5) + (tid >> 3);
-    if (FULL || widx < ((td.numel + 31) >> 5)) td.mask[widx] = v;
+    if (FULL || widx < ((td.numel + 31) >> 5)) as_global<uint32_t>(td.mask)[widx] = v;
   }
 }
 

@@ -46,13 +46,29 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return u2f(b << 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
+// Tensor pointers reach the kernels through tables in memory, so the compiler cannot tell that they
+// point to global memory and would emit FLAT accesses.  A wavefront cannot count flat loads back
+// one by one (they may be served by another memory), so it waits for ALL its outstanding loads
+// before it uses the first result -- in the middle of a batch of loads that serialises their
+// latencies.  Every tensor is device (global) memory by the library's contract: say so.
+#define TA_GLOBAL __attribute__((address_space(1)))
+
+template <typename T>
+__device__ __forceinline__ const TA_GLOBAL T* as_global(const void* p) {
+  return (const TA_GLOBAL T*)(p);
+}
+template <typename T>
+__device__ __forceinline__ TA_GLOBAL T* as_global(void* p) {
+  return (TA_GLOBAL T*)(p);
+}
+
 template <int DT>
 __device__ __forceinline__ void load4(const void* base, int64_t idx, float out[4]) {
   if constexpr (DT == kFP32) {
-    const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(static_cast<const float*>(base) + idx));
+    const v4f v = __builtin_nontemporal_load(as_global<v4f>(static_cast<const float*>(base) + idx));
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
   } else {
-    const v2u v = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(static_cast<const uint16_t*>(base) + idx));
+    const v2u v = __builtin_nontemporal_load(as_global<v2u>(static_cast<const uint16_t*>(base) + idx));
     const uint32_t h0 = v.x & 0xffffu, h1 = v.x >> 16, h2 = v.y & 0xffffu, h3 = v.y >> 16;
     if constexpr (DT == kBF16) {
       out[0] = bf16_bits_to_f32(h0); out[1] = bf16_bits_to_f32(h1);
@@ -66,8 +82,8 @@ __device__ __forceinline__ void load4(const void* base, int64_t idx, float out[4
 
 template <int DT>
 __device__ __forceinline__ float load1(const void* base, int64_t idx) {
-  if constexpr (DT == kFP32) return static_cast<const float*>(base)[idx];
-  const uint32_t h = static_cast<const uint16_t*>(base)[idx];
+  if constexpr (DT == kFP32) return as_global<float>(base)[idx];
+  const uint32_t h = as_global<uint16_t>(base)[idx];
   if constexpr (DT == kBF16) return bf16_bits_to_f32(h);
   return f16_bits_to_f32(h);
 }
@@ -77,7 +93,7 @@ __device__ __forceinline__ void store4(void* base, int64_t idx, const float v[4]
   if constexpr (DT == kFP32) {
     v4f o;
     o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3];
-    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(static_cast<float*>(base) + idx));
+    __builtin_nontemporal_store(o, as_global<v4f>(static_cast<float*>(base) + idx));
   } else {
     uint32_t h[4];
 #pragma unroll
@@ -85,15 +101,15 @@ __device__ __forceinline__ void store4(void* base, int64_t idx, const float v[4]
     v2u o;
     o.x = h[0] | (h[1] << 16);
     o.y = h[2] | (h[3] << 16);
-    __builtin_nontemporal_store(o, reinterpret_cast<v2u*>(static_cast<uint16_t*>(base) + idx));
+    __builtin_nontemporal_store(o, as_global<v2u>(static_cast<uint16_t*>(base) + idx));
   }
 }
 
 template <int DT>
 __device__ __forceinline__ void store1(void* base, int64_t idx, float v) {
-  if constexpr (DT == kFP32) static_cast<float*>(base)[idx] = v;
-  else if constexpr (DT == kBF16) static_cast<uint16_t*>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
-  else static_cast<uint16_t*>(base)[idx] = static_cast<uint16_t>(f32_to_f16_bits(v));
+  if constexpr (DT == kFP32) as_global<float>(base)[idx] = v;
+  else if constexpr (DT == kBF16) as_global<uint16_t>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
+  else as_global<uint16_t>(base)[idx] = static_cast<uint16_t>(f32_to_f16_bits(v));
 }
 
 // Guarded variants for the ragged end of a tensor: elements at or beyond `n` read as `fill`

@@ -33,18 +33,21 @@ template <int GD, int PD, bool FULL, bool MOM, bool ELEM>
 __device__ __forceinline__ void update_load(const TensorDesc& td, int64_t base, float inv_scale, float wd, float mu,
                                             const StepSize& ss, int tid, ChunkRegs& r) {
   float g[kRows][4], h[ELEM ? kRows : 1][4];
+  // Row by row, the arrays interleaved.  (Measured over 48 placements of the arrays in memory each,
+  // with the accesses in the global address space: issuing the loads array by array instead is 2 %
+  // slower on average, rotating the row order between the arrays changes nothing.)
 #pragma unroll
   for (int q = 0; q < kRows; ++q) {
     const int64_t idx = base + q * kRowElems + tid * kVec;
-    if (FULL) {
+    if constexpr (FULL) {
       load4<GD>(td.grad, idx, g[q]);
       load4<PD>(td.param, idx, r.th[q]);
-      if (MOM) load4<kFP32>(td.mom, idx, r.m[q]);
+      if constexpr (MOM) load4<kFP32>(td.mom, idx, r.m[q]);
       if constexpr (ELEM) load4<kFP32>(td.curv, idx, h[q]);
     } else {
       load4_guard<GD>(td.grad, idx, td.numel, 0.0f, g[q]);
       load4_guard<PD>(td.param, idx, td.numel, 0.0f, r.th[q]);
-      if (MOM) load4_guard<kFP32>(td.mom, idx, td.numel, 0.0f, r.m[q]);
+      if constexpr (MOM) load4_guard<kFP32>(td.mom, idx, td.numel, 0.0f, r.m[q]);
       if constexpr (ELEM) load4_guard<kFP32>(td.curv, idx, td.numel, 0.0f, h[q]);
     }
   }
@@ -73,12 +76,12 @@ __device__ __forceinline__ void update_store(const TensorDesc& td, int64_t base,
 #pragma unroll
   for (int q = 0; q < kRows; ++q) {
     const int64_t idx = base + q * kRowElems + tid * kVec;
-    if (FULL) {
+    if constexpr (FULL) {
       store4<ND>(td.param, idx, r.th[q]);
-      if (MOM) store4<kFP32>(td.mom, idx, r.m[q]);
+      if constexpr (MOM) store4<kFP32>(td.mom, idx, r.m[q]);
     } else {
       store4_guard<ND>(td.param, idx, td.numel, r.th[q]);
-      if (MOM) store4_guard<kFP32>(td.mom, idx, td.numel, r.m[q]);
+      if constexpr (MOM) store4_guard<kFP32>(td.mom, idx, td.numel, r.m[q]);
     }
   }
 }

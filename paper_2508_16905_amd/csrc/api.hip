@@ -182,7 +182,9 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
     // fallback radix select: two rounds at full width (a first window, then a refinement or the
     // other side of a window that missed); rarer further rounds are made inside the second launch.
     // Each launch leaves at once when no tensor is (still) in histogram mode.
-    TA_HIP(launch_hist_pass(T, sa, 0, s));
+    // A set bound by its number of launches gets one: rounds beyond the first are then made by the
+    // scanning workgroup alone.
+    if (T.total_chunks >= kLaunchBoundChunks) TA_HIP(launch_hist_pass(T, sa, 0, s));
     TA_HIP(launch_hist_pass(T, sa, 8, s));
   }
   const bool elem = h->cfg.elementwise_scale == 1;
@@ -198,7 +200,6 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[6], s));
   if (any_probe && !elem) TA_HIP(launch_select_finish(T, sa, h->hp.beta_curv, s));
   if (ev && level == 1) TA_HIP(hipEventRecord(ev[7], s));
-  TA_HIP(hipMemcpyAsync(h->pinned_res, T.glob, sizeof(GlobalDev), hipMemcpyDeviceToHost, s));
   return TRIACCEL_OK;
 }
 
@@ -416,6 +417,8 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   e = hipHostMalloc(reinterpret_cast<void**>(&c->pinned_res), sizeof(GlobalDev), hipHostMallocDefault);
   if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(result)"));
   std::memset(c->pinned_res, 0, sizeof(GlobalDev));
+  e = hipHostGetDevicePointer(reinterpret_cast<void**>(&T.host_result), c->pinned_res, 0);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipHostGetDevicePointer(result)"));
   e = hipDeviceSynchronize();
   if (e != hipSuccess) return fail(hip_fail(e, "hipDeviceSynchronize"));
   *out = c;

@@ -14,6 +14,9 @@ constexpr int kRowElems = kThreads * kVec;   // 1024
 constexpr int kChunk = kRowElems * kRows;    // 4096
 constexpr int kWave = 64;
 constexpr int kFinishThreads = 1024;          // workgroup of the per-tensor threshold-resolution kernel
+// Sets below this many chunks (67 M parameters) are bound by the number of dependent launches, not
+// by memory bandwidth: for them the step makes fewer, longer launches.
+constexpr uint32_t kLaunchBoundChunks = 16384;
 
 // Radix-select parameters: magnitudes are 31-bit keys (sign bit cleared).
 constexpr int kHistBins = 2048;

@@ -14,6 +14,7 @@ struct DeviceTables {
   EmaPartial* ema_partials;  // one record per chunk, written by the EMA kernel
   LayerDev* layers;
   GlobalDev* glob;
+  GlobalDev* host_result;  // pinned host memory (device-visible address): the per-layer kernel leaves the step's result record there
   uint32_t* hist;        // n_tensors x kHistBins
   Candidate* cands;      // pool: per tensor kCandLists * sub_cap + cand_cap entries
   uint32_t* cand_counters;  // n_tensors x (kCandLists + 1) counters, kCandCounterStride words apart

@@ -955,8 +955,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_select_finish(const TensorDe
 __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict__ tds,
                                                     const StatPartial* __restrict__ partials,
                                                     const EmaPartial* __restrict__ ema_partials, uint32_t* counters,
-                                                    LayerDev* layers, GlobalDev* glob, uint32_t* trans_list,
-                                                    uint32_t n_tensors, StepArg sa, Hyper hp) {
+                                                    LayerDev* layers, GlobalDev* glob, GlobalDev* host_result,
+                                                    uint32_t* trans_list, uint32_t n_tensors, StepArg sa, Hyper hp) {
   const StepScalars sc = step_scalars(sa);
   const uint32_t l = blockIdx.x;
   const TensorDesc td = tds[l];
@@ -1038,6 +1038,11 @@ __global__ __launch_bounds__(kThreads) void k_layer(const TensorDesc* __restrict
     glob->res_skipped = skip ? 1 : 0;
     glob->res_next_scale = next;
     glob->res_step_id = sc.step_id;
+    // the host's copy, written straight into pinned host memory (read after the stream has been
+    // waited for): no separate device-to-host copy in the stream
+    host_result->res_skipped = skip ? 1 : 0;
+    host_result->res_next_scale = next;
+    host_result->res_step_id = sc.step_id;
   }
 }
 
@@ -1080,7 +1085,7 @@ hipError_t launch_select_finish(const DeviceTables& t, const StepArg& sa, float 
 
 hipError_t launch_layer(const DeviceTables& t, const StepArg& sa, const Hyper& hp, hipStream_t s) {
   hipLaunchKernelGGL(k_layer, dim3(t.n_tensors), dim3(kThreads), 0, s, t.tensors, t.partials, t.ema_partials,
-                     t.cand_counters, t.layers, t.glob, t.trans_list, t.n_tensors, sa, hp);
+                     t.cand_counters, t.layers, t.glob, t.host_result, t.trans_list, t.n_tensors, sa, hp);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

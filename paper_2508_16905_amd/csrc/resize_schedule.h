@@ -34,6 +34,7 @@ constexpr uint32_t kResizeMaxStages = 8;     // stage 0 plus up to 7 subtree sta
 constexpr uint32_t kResizeTop = 16;          // chunks of stage 0 when subtree stages follow
 constexpr uint32_t kResizeTopOnly = 128;     // tensors up to this many chunks: stage 0 alone
 constexpr uint32_t kResizeBigSet = 16384;    // chunks in the whole set from which a launch more costs nothing
+                                             // (= kLaunchBoundChunks of the step's other kernels)
 
 struct ResizePlan {
   uint32_t n_stages;                  // 1 + number of subtree stages

@@ -423,6 +423,30 @@ def test_threshold_prediction_settles_within_a_few_probes():
     assert all(h >= 15 for h in held), held   # of 20 steps
 
 
+def test_curvature_refreshed_every_200th_step():
+    """The paper's own schedule (Sec. 4.1: curvature every T = 200 iterations): 1401 steps with a probe on
+    steps 1, 201, ..., 1401 (eight probes) on two multi-million-element tensors.  Every probed step and
+    every 25th step in between is compared with the oracle element by element, the result record at every
+    step.  The threshold predictor only sees probed steps, so it must behave as with a probe every step:
+    no usable prediction for the first three probes, then the predicted band settles the threshold in
+    the pass that updates the curvature (diagnostic code 1), with at most one miss among the last four."""
+    sizes = [300007, 1100003]
+    wl = custom(sizes, name="large_streaming", steps=1401)
+    p = Pair(wl)
+    outcomes = []
+    for t in range(1, 1402):
+        probe = (t - 1) % 200 == 0
+        g, z, hz = p.inputs(t, probe=probe)
+        p.step(g, z, hz, check=probe or t % 25 == 0, label=f"t={t}")
+        if probe:
+            outcomes.append([int(s.sel_outcome) for s in p.gpu.layer_state()])
+    p.close()
+    assert len(outcomes) == 8
+    assert all(o != 1 for o in outcomes[0]), outcomes            # the first probe has nothing to predict from
+    for l in range(len(sizes)):
+        assert sum(o[l] == 1 for o in outcomes[4:]) >= 3, outcomes
+
+
 @pytest.mark.parametrize("seed", [5, 23, 27, 28])
 def test_selection_under_ties_zeros_and_jumps(seed):
     """Multi-million-element tensors whose curvature samples are, at random steps, rescaled by

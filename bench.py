@@ -238,8 +238,12 @@ def main():
                     help="only the headline measurement (profiler runs); by default the large_streaming run also "
                          "measures the set in its other regimes, a few steps each, into `variants`")
     ap.add_argument("--tensors", type=int, default=0, help="use only the first N tensors of the workload (tuning runs)")
-    ap.add_argument("--mode", choices=["step", "power"], default="step",
-                    help="step: the fused optimizer step (default, the headline); power: one power iteration")
+    ap.add_argument("--mode", choices=["step", "power", "placements"], default="step",
+                    help="step: the fused optimizer step (default, the headline); power: one power iteration; "
+                         "placements: the update kernel's time over several placements of the optimizer state in "
+                         "memory (the state is released to the driver and allocated anew behind a junk allocation "
+                         "of random size, inside this one process; steps without a probe)")
+    ap.add_argument("--placements", type=int, default=12, help="--mode placements: how many placements to time")
     ap.add_argument("--power-k", type=int, default=5, help="vectors per layer in --mode power (the paper's top-k = 5)")
     ap.add_argument("--power-stage-times", action="store_true",
                     help="--mode power: read the kernel times after every call (synchronises each call)")
@@ -278,6 +282,8 @@ def main():
     K, W = args.steps, args.warmup
     if args.mode == "power":
         return bench_power(args, wl, hyper, dev)
+    if args.mode == "placements":
+        return bench_placements(args, wl, hyper, dev)
     L, N = wl.n_tensors, wl.total_params
     scale = float(hyper["loss_scale"])
     R = max(1, min(args.input_sets, K + max(W, args.settle)))
@@ -301,7 +307,10 @@ def main():
     opt = run.opt
     # In the timed region only the dominant kernel (update + cast) is bracketed by HIP events: every
     # recorded event costs the stream a few microseconds.  A graph replay carries no events at all.
-    if not args.graph:
+    # On the small sets (a step of ~0.1 ms) the two events would be a tenth of what is measured: their
+    # timed region carries none, and the kernel time comes from the breakdown steps afterwards.
+    events_in_timed_region = not args.graph and N >= 67_000_000
+    if events_in_timed_region:
         opt.set_profiling(1 if args.switch_stress else 2)
 
     # bring the run to its steady state first when the warm-up alone is shorter than that takes
@@ -316,8 +325,8 @@ def main():
     res = opt.result()
     assert not res.skipped and res.step_index == P + W + K
     KP = min(K, 63)  # the library keeps the event times of the last 64 steps
-    upd_ms_timed = None if args.graph else sum(opt.stage_times(back)[4] for back in range(KP)) / KP
-    resize_ms_timed = sum(opt.stage_times(back)[5] for back in range(KP)) / KP if args.switch_stress and not args.graph else None
+    upd_ms_timed = sum(opt.stage_times(back)[4] for back in range(KP)) / KP if events_in_timed_region else None
+    resize_ms_timed = sum(opt.stage_times(back)[5] for back in range(KP)) / KP if args.switch_stress and events_in_timed_region else None
     # stage breakdown: the same number of steps again, launched kernel by kernel with an event at
     # every stage boundary (not part of the timed region)
     opt.set_profiling(1)
@@ -386,7 +395,8 @@ def main():
             "bound": "hbm",
             "kernel": dominant,
             "kernel_ms": upd_ms,
-            "kernel_ms_from": "HIP events in the steps after the timed region (a graph replay carries none)"
+            "kernel_ms_from": "HIP events in the steps after the timed region (the timed region of a graph replay or of a "
+                              "small set carries none)"
                               if upd_ms_timed is None else "HIP events around the kernel in the timed region",
             "achieved": upd_gbps,
             "peak": HBM_PEAK_GBPS,
@@ -533,6 +543,49 @@ def variants(run, wl, hyper, sets, dev, K):
     v["mixed_state"]["workload"] = f"{wm.n_tensors} tensors, {wm.total_params} params, fp16 gradients"
     r.close()
     return v
+
+
+PLACEMENT_WARM, PLACEMENT_TIMED = 4, 12
+
+
+def bench_placements(args, wl, hyper, dev):
+    """The update kernel has a faster and a slower regime, and which one a run gets depends on where the
+    arrays it streams lie in memory: same process, same kernel, same inputs, only the optimizer state
+    allocated anew.  Each placement launches the kernel PLACEMENT_WARM + PLACEMENT_TIMED times (steps
+    without a probe: statistics, per-layer kernel, update), so the dispatches of a profiler's counter file
+    can be grouped by placement."""
+    import random
+
+    import torch
+
+    N = wl.total_params
+    sets = build_sets(wl, 4, float(hyper["loss_scale"]), dev, fisher=True)   # gradients only
+    rs = random.Random(os.getpid())
+    junk, rows = None, []
+    for k in range(args.placements):
+        run = Runner(wl, hyper, sets, dev)
+        run.opt.set_profiling(2)
+        run.run(PLACEMENT_WARM, probe=False)
+        run.run(PLACEMENT_TIMED, probe=False)
+        run.opt.result()
+        ms = sorted(run.opt.stage_times(b)[4] for b in range(PLACEMENT_TIMED))
+        state = run.opt.layer_state()
+        size = lambda c: 4 if c == 2 else 2
+        nbytes = sum(n * (run.grad_size + size(s.prev_code) + size(s.code) + 8) for n, s in zip(run.numel, state))
+        rows.append({"placement": k, "k_update_ms_median": ms[len(ms) // 2], "GBps": nbytes / 1e9 / (ms[len(ms) // 2] / 1e3),
+                     "junk_bytes_before": 0 if junk is None else junk.numel(),
+                     "param0": hex(run.opt.buf[0].data_ptr()), "grad0": hex(sets[0][0][0].data_ptr())})
+        run.close()
+        del run, junk
+        torch.cuda.empty_cache()
+        junk = torch.empty(rs.randrange(1, 4000) * (1 << 20) + rs.randrange(0, 512) * 4096, dtype=torch.uint8, device=dev)
+    t = sorted(r["k_update_ms_median"] for r in rows)
+    print(json.dumps({
+        "metric": "k_update time over placements of the optimizer state in memory (ms, steps without a probe)",
+        "workload": f"{wl.name}: {wl.n_tensors} tensors, {N} params" + (", every layer FP32" if args.all_fp32 else ""),
+        "launches_of_k_update_per_placement": PLACEMENT_WARM + PLACEMENT_TIMED,
+        "min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1], "mean_ms": sum(t) / len(t),
+        "placements": rows}))
 
 
 def bench_power(args, wl, hyper, dev):

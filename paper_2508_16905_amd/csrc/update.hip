@@ -1,7 +1,7 @@
 // gfx950 kernels of the fused update + cast (stage 5 of the optimizer step) and the stand-alone
 // mask pass.  Compiled as a translation unit of its own: the update body is specialised for every
 // (gradient, old, new) precision triple, which dominates the build time.
-#include "update_body.h"
+#include "resize_body.h"
 
 namespace triaccel {
 
@@ -36,16 +36,28 @@ __global__ __launch_bounds__(kThreads) void k_mask_pass(const TensorDesc* __rest
 // kernel (nothing in the update depends on the mask, and a separate launch would cost a full
 // grid of idle workgroups on every step that needs no fallback).
 //
+// The first `resize_wgs` workgroups of the grid do something else: the first launch of the in-place
+// resize of the tensors whose storage size does change (resize_body.h).  It depends on the per-layer
+// kernel only, like the update itself, so it needs no launch of its own; it comes first in the grid
+// because its work items are the longer ones.
+//
 // In the element-wise form (ELEM) the threshold must be final before the update, so the mask and
 // the listed keys are completed by the kernels before this one and no mask pass runs here.
 template <bool ELEM>
 __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restrict__ tds,
                                                      const ChunkRef* __restrict__ chunks, LayerDev* layers,
                                                      const GlobalDev* glob, Candidate* cands, uint32_t* counters,
-                                                     StepArg sa, float wd, float mu, float alpha) {
+                                                     const uint32_t* trans_list, uint32_t n_tensors, ResizePlan plan,
+                                                     uint32_t resize_slots, uint32_t resize_wgs, StepArg sa, float wd,
+                                                     float mu, float alpha) {
   const StepScalars sc = step_scalars(sa);
   if (step_skipped(glob, sc.step_id)) return;
-  const ChunkRef cr = chunks[blockIdx.x];
+  if (blockIdx.x < resize_wgs) {
+    resize_items<ELEM>(tds, layers, glob, trans_list, n_tensors, plan, 0u, resize_slots, blockIdx.x, resize_wgs, sc, wd, mu,
+                       alpha);
+    return;
+  }
+  const ChunkRef cr = chunks[blockIdx.x - resize_wgs];
   LayerDev& ls = layers[cr.tensor];
   const int pd = ls.prev_code, nd = ls.code;
   const TensorDesc td = tds[cr.tensor];
@@ -65,12 +77,15 @@ __global__ __launch_bounds__(kThreads) void k_update(const TensorDesc* __restric
 
 hipError_t launch_update(const DeviceTables& t, const StepArg& sa, float wd, float mu, float alpha, bool elem,
                          hipStream_t s) {
+  const ResizePlan plan = make_resize_plan(t.max_chunks_per_tensor, t.total_chunks);
+  const ResizeGrid rg = resize_grid(plan, 0u, t.n_tensors);
+  const dim3 grid(t.total_chunks + rg.grid);
   if (elem)
-    hipLaunchKernelGGL(k_update<true>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob,
-                       t.cands, t.cand_counters, sa, wd, mu, alpha);
+    hipLaunchKernelGGL(k_update<true>, grid, dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob, t.cands,
+                       t.cand_counters, t.trans_list, t.n_tensors, plan, rg.slots, rg.grid, sa, wd, mu, alpha);
   else
-    hipLaunchKernelGGL(k_update<false>, dim3(t.total_chunks), dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers,
-                       t.glob, t.cands, t.cand_counters, sa, wd, mu, alpha);
+    hipLaunchKernelGGL(k_update<false>, grid, dim3(kThreads), 0, s, t.tensors, t.chunks, t.layers, t.glob, t.cands,
+                       t.cand_counters, t.trans_list, t.n_tensors, plan, rg.slots, rg.grid, sa, wd, mu, alpha);
   TA_LAUNCH_CHECK();
   return hipSuccess;
 }

@@ -72,6 +72,29 @@ class TriAccel:
         B.triaccel_step(self.handle, self._tensors, lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes,
                         update_curvature)
 
+    def make_table(self, grads: Sequence[torch.Tensor], zs: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                   hzs: Optional[Sequence[Optional[torch.Tensor]]] = None):
+        """The tensor table of ``step`` for one set of input buffers, marshalled once: a caller whose
+        gradient and probe buffers stay where they are (the usual case in a training loop) passes it to
+        ``step_table`` at every step instead of paying for the per-tensor marshalling again."""
+        arr = (B.Tensor * self.n)()
+        for i in range(self.n):
+            src, t = self._tensors[i], arr[i]
+            t.param, t.curv, t.mom, t.mask = src.param, src.curv, src.mom, src.mask
+            t.numel, t.grad_dtype, t.param_dtype = src.numel, src.grad_dtype, src.param_dtype
+            t.grad = grads[i].data_ptr()
+            z = None if zs is None else zs[i]
+            t.z = None if z is None else z.data_ptr()
+            t.hz = None if z is None else hzs[i].data_ptr()
+        return arr, (grads, zs, hzs)   # the buffers stay alive as long as the table does
+
+    def step_table(self, table, lr: float = 0.1, loss_scale: float = 1.0, batch_size: int = 0,
+                   mem_used_bytes: int = 0, mem_total_bytes: int = 0, update_curvature: bool = True) -> None:
+        """``step`` with a table prepared by ``make_table``."""
+        self._keep = table
+        B.triaccel_step(self.handle, table[0], lr, loss_scale, batch_size, mem_used_bytes, mem_total_bytes,
+                        update_curvature)
+
     def result(self) -> B.StepResult:
         return B.triaccel_result(self.handle)
 

@@ -33,6 +33,7 @@ int hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 constexpr int kRing = 4;  // pinned staging buffers for the pointer table
+constexpr int kTableSlots = 8;  // device copies of the pointer table kept per handle
 constexpr uint64_t kMemSampleEvery = 16;  // calls between two hipMemGetInfo samples when the caller passes no figures
 
 bool valid_dtype(int32_t d) { return d == TRIACCEL_FP16 || d == TRIACCEL_BF16 || d == TRIACCEL_FP32; }
@@ -55,9 +56,17 @@ struct triaccel_ctx {
   std::vector<int64_t> numel;
   std::vector<int32_t> grad_dtype;
   DeviceTables t{};
-  std::vector<TensorDesc> desc;       // host copy of the table to upload
-  std::vector<TensorDesc> desc_sent;  // what the device currently holds
-  bool desc_valid = false;
+  std::vector<TensorDesc> desc;       // the table of the step being enqueued
+  // Device copies of the table.  A caller that alternates between a few sets of buffers (double-buffered
+  // gradients, a probe on some steps only) finds each of its tables already on the device; a table seen
+  // for the first time replaces the one used longest ago (the copy is ordered on the stream).
+  struct TableSlot {
+    TensorDesc* dev = nullptr;
+    std::vector<TensorDesc> sent;  // what the device copy holds
+    bool valid = false;            // `sent` has been enqueued for upload
+    uint64_t last_used = 0;
+  };
+  TableSlot tables[kTableSlots];
   TensorDesc* staging[kRing] = {};
   hipEvent_t staging_ev[kRing] = {};
   bool staging_used[kRing] = {};
@@ -357,7 +366,9 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   T.total_chunks = (uint32_t)chunks.size();
   T.max_chunks_per_tensor = max_chunks;
   T.persistent_grid = cus * 8;
-  if ((rc = dev_alloc(c, &T.tensors, (size_t)n))) return fail(rc);
+  for (auto& slot : c->tables)
+    if ((rc = dev_alloc(c, &slot.dev, (size_t)n))) return fail(rc);
+  T.tensors = c->tables[0].dev;
   if ((rc = dev_alloc(c, &T.chunks, chunks.size()))) return fail(rc);
   if ((rc = dev_alloc(c, &T.partials, chunks.size()))) return fail(rc);
   if ((rc = dev_alloc(c, &T.ema_partials, chunks.size()))) return fail(rc);
@@ -371,8 +382,10 @@ int triaccel_init(triaccel_handle* out, const triaccel_config* config, const tri
   e = hipMemcpy(T.chunks, chunks.data(), chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(chunks)"));
   // shapes and chunk ranges are valid from now on; the pointers arrive with every step
-  e = hipMemcpy(T.tensors, c->desc.data(), (size_t)n * sizeof(TensorDesc), hipMemcpyHostToDevice);
-  if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(tensor table)"));
+  for (auto& slot : c->tables) {
+    e = hipMemcpy(slot.dev, c->desc.data(), (size_t)n * sizeof(TensorDesc), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(tensor table)"));
+  }
   e = hipMemcpy(T.layers, c->layer_host.data(), (size_t)n * sizeof(LayerDev), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(hip_fail(e, "hipMemcpy(layers)"));
   for (int i = 0; i < kRing; ++i) {
@@ -474,21 +487,40 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
     d.has_probe = fisher ? (any_probe ? 1 : 0) : (t.z != nullptr);
   }
   const size_t table_bytes = (size_t)n * sizeof(TensorDesc);
-  if (!h->desc_valid || std::memcmp(h->desc.data(), h->desc_sent.data(), table_bytes) != 0) {
-    const int slot = h->ring_pos;
-    if (h->staging_used[slot]) TA_HIP(hipEventSynchronize(h->staging_ev[slot]));
-    std::memcpy(h->staging[slot], h->desc.data(), table_bytes);
-    h->desc_valid = false;  // until the copy below is known to be enqueued
-    TA_HIP(hipMemcpyAsync(h->t.tensors, h->staging[slot], table_bytes, hipMemcpyHostToDevice, h->stream));
-    TA_HIP(hipEventRecord(h->staging_ev[slot], h->stream));
-    h->ring_pos = (h->ring_pos + 1) % kRing;
-    h->staging_used[slot] = true;
-    h->desc_sent = h->desc;
-    h->desc_valid = true;
+  const uint64_t index = h->step_index + 1;
+  // a replayed graph has the address of the first device copy in its kernel arguments
+  const int n_slots = (h->use_graph && h->profiling == 0) ? 1 : kTableSlots;
+  int use = -1, victim = 0;
+  for (int i = 0; i < n_slots; ++i) {
+    triaccel_ctx::TableSlot& slot = h->tables[i];
+    if (slot.valid && std::memcmp(h->desc.data(), slot.sent.data(), table_bytes) == 0) {
+      use = i;
+      break;
+    }
+    if (!slot.valid) {
+      if (h->tables[victim].valid) victim = i;
+    } else if (h->tables[victim].valid && slot.last_used < h->tables[victim].last_used) {
+      victim = i;
+    }
   }
+  if (use < 0) {
+    triaccel_ctx::TableSlot& slot = h->tables[victim];
+    const int stage = h->ring_pos;
+    if (h->staging_used[stage]) TA_HIP(hipEventSynchronize(h->staging_ev[stage]));
+    std::memcpy(h->staging[stage], h->desc.data(), table_bytes);
+    slot.valid = false;  // until the copy below is known to be enqueued
+    TA_HIP(hipMemcpyAsync(slot.dev, h->staging[stage], table_bytes, hipMemcpyHostToDevice, h->stream));
+    TA_HIP(hipEventRecord(h->staging_ev[stage], h->stream));
+    h->ring_pos = (h->ring_pos + 1) % kRing;
+    h->staging_used[stage] = true;
+    slot.sent = h->desc;
+    slot.valid = true;
+    use = victim;
+  }
+  h->tables[use].last_used = index;
+  h->t.tensors = h->tables[use].dev;
 
   // the call counts, and its result can be read, only once all of its work is enqueued
-  const uint64_t index = h->step_index + 1;
   StepScalars sc{};
   sc.lr = args->lr;
   sc.loss_scale = args->loss_scale;

@@ -34,16 +34,16 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by what the same
 # counters read for the library's plain copy kernel; see the summaries under profiles/).  They belong
 # to the kernel sources with the digest below: when the sources differ, `traffic` is null.
-STEP_SOURCES = ("update.hip", "update_body.h", "device_util.h", "numerics.h")
+STEP_SOURCES = ("update.hip", "update_body.h", "resize_body.h", "resize_schedule.h", "device_util.h", "numerics.h")
 POWER_SOURCES = ("power.hip", "power.h", "numerics.h")
 MEASURED_TRAFFIC = {
     # k_update<false>, default run of the large_streaming workload
-    "step": {"sources_sha256": "1d24179a83d2f96c1c1e782a979bfaf51cdd8a86bc295c56e0f805b84788eb52", "workload": "large_streaming",
+    "step": {"sources_sha256": "16a0fc49e758ec5b6e4b2ab216d26cd137125df31f6cbaf06a31275dd758259e", "workload": "large_streaming",
              "alg_bytes": 18991808512, "fetch_bytes": 11.677e9, "write_bytes": 7.348e9,
              "from": "profiles/fused_step_large_streaming_hbm_counters.md"},
     # k_power_apply<5> / k_power_gram<5>, --mode power on the large_streaming workload
-    "power": {"sources_sha256": "5cbb185eadd41b14669fb62e658695710a4237dcda5f869e3390ed3ea3047578", "workload": "large_streaming",
-              "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.48e9},
+    "power": {"sources_sha256": "1bf257dfb3af1e77ee28322071abf703d828084ae8edeb4fa6b9f98da079a634", "workload": "large_streaming",
+              "k_power_apply": {"fetch_bytes": 21.51e9, "write_bytes": 21.47e9},
               "k_power_gram": {"fetch_bytes": 42.95e9, "write_bytes": 0.01e9},
               "from": "profiles/power_iteration_large_streaming_k5.md"},
 }

@@ -164,6 +164,8 @@ class Runner:
         if probe:
             pi = self.probes % len(self.sets)
             self.probes += 1
+        if self.fisher:
+            pi = None   # the curvature sample is the gradient itself: no probe pairs in this mode
         table = self.tables.get((gi, pi))
         if table is None:
             z = hz = None
@@ -504,6 +506,16 @@ def variants(run, wl, hyper, sets, dev, K):
     v["all_fp32"] = f
     r.close()
 
+    # (3b) the other curvature source and the other form of the step size (same inputs)
+    for name, extra in (("fisher", dict(curvature_source=1)), ("elementwise", dict(elementwise_scale=1))):
+        r = Runner(wl, dict(hyper, **extra), sets, dev)
+        r.opt.set_profiling(2)
+        r.run(64)
+        ms = r.timed(K)
+        v[name] = r.figures(ms, True)
+        v[name]["k_update_ms"] = sum(r.opt.stage_times(b)[4] for b in range(K)) / K
+        r.close()
+
     # (4) the first steps of a run: no threshold prediction yet, every tensor goes through the fallback
     r = Runner(wl, hyper, sets, dev)
     first = []
@@ -546,6 +558,9 @@ def variants(run, wl, hyper, sets, dev, K):
     del r
     sets.clear()
     torch.cuda.empty_cache()
+
+    # (5b) one power iteration on k = 5 vectors per tensor (Sec. 3.2; 43 GB of vectors)
+    v["power_iteration_k5"] = power_variant(wl, hyper, dev, 5, max(3, K // 2))
 
     # (6) the mixed-state set: fp16 gradients, three storage formats
     wm = get_workload("mixed_state")
@@ -602,6 +617,41 @@ def bench_placements(args, wl, hyper, dev):
         "launches_of_k_update_per_placement": PLACEMENT_WARM + PLACEMENT_TIMED,
         "min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1], "mean_ms": sum(t) / len(t),
         "placements": rows}))
+
+
+def power_variant(wl, hyper, dev, k, K):
+    """Short form of --mode power for the `variants` record: ms per iteration and the two passes."""
+    import torch
+
+    import paper_2508_16905_amd as ta
+
+    L, N = wl.n_tensors, wl.total_params
+    opt = ta.TriAccel(dict(hyper, power_k=k), [wl.init_param(l, device=dev) for l in range(L)], grad_dtype=wl.grad_dtype)
+    us = [wl.power_start(l, k, device=dev) for l in range(L)]
+    hus = []
+    for l in range(L):
+        g = torch.Generator(device=dev)
+        g.manual_seed(1000 + l)
+        h = torch.zeros_like(us[l])
+        h[:, : wl.numel(l)] = torch.randn(k, wl.numel(l), generator=g, device=dev) * float(wl.layer_consts(l).get("d", 1.0))
+        hus.append(h)
+    opt.set_profiling(True)
+    for _ in range(2):
+        opt.power_iter(us, hus, k)
+    torch.cuda.synchronize()
+    stage = [0.0, 0.0, 0.0]
+    t0 = time.perf_counter()
+    for _ in range(K):
+        opt.power_iter(us, hus, k)
+        stage = [a + b for a, b in zip(stage, opt.power_times())]   # synchronises each call
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    stage = [x / K for x in stage]
+    opt.close()
+    pass_bytes = 8.0 * k * N
+    return {"ms_per_iteration": ms, "params_per_s": N / (ms / 1e3), "bytes_per_param": 16.0 * k,
+            "gram_ms": stage[0], "gram_frac_of_peak": pass_bytes / 1e9 / (stage[0] / 1e3) / HBM_PEAK_GBPS,
+            "apply_ms": stage[2], "apply_frac_of_peak": pass_bytes / 1e9 / (stage[2] / 1e3) / HBM_PEAK_GBPS,
+            "frac_of_peak": 2 * pass_bytes / 1e9 / ((stage[0] + stage[1] + stage[2]) / 1e3) / HBM_PEAK_GBPS}
 
 
 def bench_power(args, wl, hyper, dev):

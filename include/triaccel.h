@@ -177,7 +177,8 @@ typedef struct {
  * Create a handle for n tensors.  `tensors` gives shapes, dtypes and the initial pointers;
  * curv / mom / mask contents are taken as the initial state (normally zero).  `hip_stream` is a
  * hipStream_t (NULL = the default stream).  Allocates the workspace (chunk table, partials,
- * histograms, candidate lists, per-layer state; a few MB plus 16 bytes per 4096 parameters).
+ * histograms, candidate lists, per-layer state, eight device copies of the tensor table; a few MB plus
+ * 40 bytes per 4096 parameters, plus up to 4 MB of candidate lists per tensor of 262,144 elements or more).
  */
 int triaccel_init(triaccel_handle *out, const triaccel_config *config, const triaccel_tensor *tensors,
                   int32_t n, void *hip_stream);

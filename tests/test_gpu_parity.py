@@ -105,9 +105,11 @@ def test_half_precision_gradients(gd):
 
 def test_every_precision_transition_in_place():
     # initial dtypes x codes forced by the thresholds: each run sends all tensors to one code
-    # up to 256 chunks a tensor is rewritten by one workgroup, beyond that phase by phase: 1100003
-    # elements are 269 chunks (one phase launch); the later phases are covered at full size
-    sizes = [1, 7, 4096, 4097, 8192, 8193, 20000, 140000, 64 * 4096, 64 * 4096 + 1, 300007, 1100003]
+    # 128 chunks is the largest tensor rewritten by one workgroup alone; beyond it subtrees of chunks take over
+    # (roots 16..31): 129 chunks, one level and a ragged second (513 chunks: levels of 1..16 chunks, the last cut
+    # short), and 1025 chunks (a single chunk in the deepest level of one subtree only)
+    sizes = [1, 7, 4096, 4097, 8192, 8193, 20000, 140000, 64 * 4096, 64 * 4096 + 1, 300007, 128 * 4096, 128 * 4096 + 1,
+             1100003, 513 * 4096 - 5, 1024 * 4096 + 9]
     for target, (lo, hi) in {FP16: (1e30, 1e31), BF16: (0.0, 1e30), FP32: (0.0, 0.0)}.items():
         for init in (FP16, BF16, FP32):
             wl = custom(sizes, param_dtypes=[init] * len(sizes), tau_low=lo, tau_high=hi, tau_curv=1e30)

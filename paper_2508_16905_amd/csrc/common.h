@@ -127,7 +127,7 @@ struct LayerDev {
   uint32_t nonzero;        // number of non-zero keys
   uint32_t dens_count, dens_width;  // key density near theta: dens_count keys per dens_width keys
   uint32_t count_above;    // the next histogram pass must count the keys above its window
-  uint32_t hist_arrived;   // chunks whose keys are in this round's histogram (cleared by the scan)
+  uint32_t hist_arrived;   // chunks whose keys are in the histogram of the pass under way (cleared by the scan)
   // accumulators filled by atomics during a step and cleared by the kernel that consumes them
   uint32_t acc_above, acc_maxkey, acc_nonfinite;
 };

@@ -39,16 +39,19 @@ __device__ __forceinline__ Moments shfl_down(const Moments& m, int o) {
 // wavefronts are added in a fixed order; one (mean, M2) partial per chunk.
 // ---------------------------------------------------------------------------------------------
 template <int GD, bool FULL>
-__device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, float inv_scale, double shift,
+__device__ __forceinline__ void stats_chunk(const TensorDesc& td, int64_t base, float inv_scale, double& shift,
                                             double& s1, double& s2, uint32_t& bad) {
   const int tid = threadIdx.x;
   float g[kRows][4];
+  // the shift is read in the same batch of loads as the data: one memory latency per chunk, not two
+  const float first = load1<GD>(td.grad, base);
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = base + r * kRowElems + tid * kVec;
     if (FULL) load4<GD>(td.grad, idx, g[r]);
     else load4_guard<GD>(td.grad, idx, td.numel, 0.0f, g[r]);
   }
+  shift = (double)(first * inv_scale);
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
 #pragma unroll
@@ -82,12 +85,7 @@ __global__ __launch_bounds__(kThreads) void k_grad_stats(const TensorDesc* __res
   const bool full = base + kChunk <= td.numel;
   double s1 = 0.0, s2 = 0.0;
   uint32_t bad = 0;
-  double shift;
-  switch (td.grad_dtype) {
-    case kFP32: shift = (double)(load1<kFP32>(td.grad, base) * sc.inv_scale); break;
-    case kBF16: shift = (double)(load1<kBF16>(td.grad, base) * sc.inv_scale); break;
-    default: shift = (double)(load1<kFP16>(td.grad, base) * sc.inv_scale); break;
-  }
+  double shift = 0.0;
   if (full) {
     switch (td.grad_dtype) {
       case kFP32: stats_chunk<kFP32, true>(td, base, sc.inv_scale, shift, s1, s2, bad); break;

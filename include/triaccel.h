@@ -210,9 +210,10 @@ const char *triaccel_strerror(int code);
 const char *triaccel_last_error(void);
 
 /*
- * on != 0: the following triaccel_step calls replay the step as a HIP graph (captured at the first such
- * call, one graph for steps that refresh the curvature and one for steps that do not) instead of
- * launching its kernels one by one; results are identical.  Meant for small parameter sets, where the
+ * on != 0: the following triaccel_step calls replay the step as a HIP graph instead of launching its
+ * kernels one by one; results are identical.  A graph is captured the first time it is needed: one for
+ * steps that refresh the curvature and one for steps that do not, for each of the (up to eight) device
+ * copies of the tensor table in use.  Meant for small parameter sets, where the
  * step is bound by launch overhead.  While profiling is on the kernels are launched one by one.
  * The handle must have been created on a stream of its own (the default stream cannot be captured).
  */

@@ -83,7 +83,9 @@ struct triaccel_ctx {
   std::vector<LayerDev> layer_host;
   std::vector<void*> device_allocs;
   bool use_graph = false;
-  StepGraph graphs[2];  // [0] steps without a curvature refresh, [1] with
+  // One captured step per (variant, device copy of the table): [0][s] steps without a curvature
+  // refresh, [1][s] with; the kernels of a captured step hold the address of table copy s.
+  StepGraph graphs[2][kTableSlots];
   // power iteration (only with cfg.power_k > 0)
   PowerTables pt{};
   PowerDesc* power_staging[kRing] = {};
@@ -159,10 +161,11 @@ void free_ctx(triaccel_ctx* c) {
     if (c->power_ev[i]) (void)hipEventDestroy(c->power_ev[i]);
     if (c->power_prof[i]) (void)hipEventDestroy(c->power_prof[i]);
   }
-  for (auto& g : c->graphs) {
-    if (g.exec) (void)hipGraphExecDestroy(g.exec);
-    if (g.graph) (void)hipGraphDestroy(g.graph);
-  }
+  for (auto& variant : c->graphs)
+    for (auto& g : variant) {
+      if (g.exec) (void)hipGraphExecDestroy(g.exec);
+      if (g.graph) (void)hipGraphDestroy(g.graph);
+    }
   if (c->pinned_res) (void)hipHostFree(c->pinned_res);
   for (auto& set : c->ev)
     for (auto& e : set)
@@ -212,11 +215,12 @@ int enqueue_step(triaccel_ctx* h, const StepArg& sa, bool any_probe, hipEvent_t*
   return TRIACCEL_OK;
 }
 
-// Graph form of the same step: captured once per variant (with / without a curvature refresh)
-// from the launches above, with the kernels reading the per-step scalars from device memory; a
-// replay updates the one node that writes those scalars and launches the graph.
-int replay_step(triaccel_ctx* h, const StepScalars& sc, bool any_probe) {
-  StepGraph& g = h->graphs[any_probe ? 1 : 0];
+// Graph form of the same step: captured once per variant (with / without a curvature refresh) and
+// device copy of the tensor table (`slot`, the one h->t.tensors points to) from the launches above,
+// with the kernels reading the per-step scalars from device memory; a replay updates the one node
+// that writes those scalars and launches the graph.
+int replay_step(triaccel_ctx* h, const StepScalars& sc, bool any_probe, int slot) {
+  StepGraph& g = h->graphs[any_probe ? 1 : 0][slot];
   hipStream_t s = h->stream;
   if (!g.exec) {
     hipGraph_t graph = nullptr;
@@ -488,10 +492,8 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   }
   const size_t table_bytes = (size_t)n * sizeof(TensorDesc);
   const uint64_t index = h->step_index + 1;
-  // a replayed graph has the address of the first device copy in its kernel arguments
-  const int n_slots = (h->use_graph && h->profiling == 0) ? 1 : kTableSlots;
   int use = -1, victim = 0;
-  for (int i = 0; i < n_slots; ++i) {
+  for (int i = 0; i < kTableSlots; ++i) {
     triaccel_ctx::TableSlot& slot = h->tables[i];
     if (slot.valid && std::memcmp(h->desc.data(), slot.sent.data(), table_bytes) == 0) {
       use = i;
@@ -529,7 +531,7 @@ int triaccel_step(triaccel_handle h, const triaccel_tensor* tensors, int32_t n, 
   const bool prof = h->profiling != 0;
   h->ev_step[index % TRIACCEL_PROFILE_RING] = 0;
   if (h->use_graph && !prof) {
-    const int rc = replay_step(h, sc, any_probe);
+    const int rc = replay_step(h, sc, any_probe, use);
     if (rc) return rc;
   } else {
     hipEvent_t* ev = prof ? h->ev[index % TRIACCEL_PROFILE_RING] : nullptr;

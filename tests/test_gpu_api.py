@@ -120,12 +120,15 @@ def test_two_runs_are_bit_identical_and_pointers_may_change():
     b.close()
 
 
-def test_prepared_tables_of_resident_buffers_revisited_in_any_order():
+@pytest.mark.parametrize("graph", [False, True], ids=["kernel_by_kernel", "graph_replay"])
+def test_prepared_tables_of_resident_buffers_revisited_in_any_order(graph):
     """Eleven resident sets of input buffers, each marshalled once (make_table) and revisited in an
     irregular order with and without a probe: more distinct pointer tables than the library keeps
     device copies of, so tables are found again, evicted and uploaded again.  Every step is compared
     with the oracle, the steps are enqueued without a wait in between (the copies are ordered on the
-    stream), and a second handle fed the same sequence through plain ``step`` ends bit-identical."""
+    stream), and a second handle fed the same sequence through plain ``step`` ends bit-identical.
+    With ``graph`` the first handle replays the step as a HIP graph (one captured step per device copy
+    of the table and variant) on a stream of its own."""
     import sys, os
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from _runner import make_oracle, to_numpy
@@ -133,9 +136,18 @@ def test_prepared_tables_of_resident_buffers_revisited_in_any_order():
 
     wl = get_workload("resnet18")
     R = 11
-    a, b = make(wl), make(wl)
+    b = make(wl)
+    if graph:
+        stream = torch.cuda.Stream(device=DEV)
+        params = [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)]
+        with torch.cuda.stream(stream):
+            a = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype, stream=stream)
+        a.set_graph(True)
+    else:
+        a = make(wl)
     orc = make_oracle(wl, workers=16)
     sets = [inputs(wl, t) for t in range(1, R + 1)]
+    torch.cuda.synchronize()  # the inputs were made on the default stream
     with_probe = [a.make_table(g, z, hz) for g, z, hz in sets]
     without = [a.make_table(g) for g, _, _ in sets]
     order = [0, 1, 0, 2, 3, 4, 5, 6, 7, 8, 9, 10, 0, 0, 5, 1, 10, 9, 2, 2, 7, 3, 0, 8]

@@ -268,3 +268,36 @@ def test_in_place_resize_through_every_phase():
         assert [(o.prev_code, o.code) for o in p.orc.tensors] == [(target, target)] * 2
         p.close()
         print(f"in-place resize {init} -> {target} ok", flush=True)
+
+
+def _switching_run(sizes, mult, workers=16):
+    """Every tensor follows the same sequence of storage precisions (variance EMA off, the gradient
+    scale picks the code); update-only steps, every element compared with the oracle."""
+    from _gpu_harness import Pair
+    from test_gpu_parity import custom
+
+    wl = custom(sizes, name="large_streaming", beta_var=0.0, tau_low=1e-4, tau_high=1e-2, tau_curv=1e30)
+    p = Pair(wl, workers=workers)
+    for t, m in enumerate(mult, start=1):
+        g, z, hz = p.inputs(t, probe=False)
+        p.step([x * (m * 3.0) for x in g], z, hz, label=f"t={t}")
+        print(f"step {t}: codes {sorted(set(p.code_hist[-1]))}", flush=True)
+    seq = [row[0] for row in p.code_hist]
+    p.close()
+    return seq
+
+
+def test_in_place_resize_with_more_work_items_than_workgroups():
+    """65 tensors of 4097 chunks narrowing, widening and narrowing again together: 65 x 1024
+    (tensor, subtree) work items in the widest launch of the rewrite, more than the 65536 workgroups a
+    launch is given, so workgroups take several items each."""
+    from workloads.configs import BF16, FP16
+
+    assert _switching_run([4096 * 4096 + 7] * 65, [0.1, 10.0, 1.0]) == [FP16, FP32, BF16]
+
+
+def test_in_place_resize_of_one_tensor_of_65540_chunks():
+    """A single tensor of 2^28 + 12345 elements: four subtree stages, the deepest with 8192 roots."""
+    from workloads.configs import BF16, FP16
+
+    assert _switching_run([(1 << 28) + 12345, 5000], [0.1, 10.0, 1.0]) == [FP16, FP32, BF16]

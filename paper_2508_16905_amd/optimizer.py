@@ -17,8 +17,9 @@ class TriAccel:
     """State of one optimizer instance: per tensor a 4*numel-byte parameter buffer, curvature EMA,
     momentum buffer and bit mask, all on the GPU."""
 
-    def __init__(self, hyper: dict, params: Sequence[torch.Tensor], grad_dtype: int = B.FP32,
+    def __init__(self, hyper: dict, params: Sequence[torch.Tensor], grad_dtype=B.FP32,
                  stream: Optional[torch.cuda.Stream] = None):
+        """``grad_dtype``: precision code of the gradients, one for all tensors or one per tensor."""
         if not torch.cuda.is_available():
             raise RuntimeError("TriAccel needs a GPU: the optimizer step runs only in the HIP library")
         B.load_library()
@@ -28,7 +29,10 @@ class TriAccel:
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self.n = len(params)
         self.numel = [int(p.numel()) for p in params]
-        self.grad_dtype = int(grad_dtype)
+        self.grad_dtype = ([int(grad_dtype)] * self.n if isinstance(grad_dtype, int)
+                           else [int(d) for d in grad_dtype])
+        if len(self.grad_dtype) != self.n:
+            raise ValueError("grad_dtype: one code, or one per tensor")
         self.init_codes = [_CODE[p.dtype] for p in params]
         self.buf: List[torch.Tensor] = []
         for p, n in zip(params, self.numel):
@@ -47,7 +51,7 @@ class TriAccel:
             t.mom = self.mom[i].data_ptr() if use_mom else None
             t.mask = self.mask[i].data_ptr()
             t.numel = self.numel[i]
-            t.grad_dtype = self.grad_dtype
+            t.grad_dtype = self.grad_dtype[i]
             t.param_dtype = self.init_codes[i]
         # init validates grad pointers too: give it any valid address (the parameter buffer)
         for i in range(self.n):

@@ -15,6 +15,7 @@ import torch
 
 import paper_2508_16905_amd as ta
 from _runner import make_oracle, to_numpy
+from workloads.configs import TORCH_DTYPE
 
 STAT_RTOL = 1e-5
 DECISION_MARGIN = 1e-4  # ten times the tolerance of the statistics
@@ -37,15 +38,18 @@ def same_or_both_nan(a: np.ndarray, b: np.ndarray) -> bool:
 
 
 class Pair:
-    def __init__(self, wl, workers=8, device="cuda:0", graph=False):
-        """``graph``: the library replays the step as a HIP graph (needs a stream of its own)."""
+    def __init__(self, wl, workers=8, device="cuda:0", graph=False, grad_dtypes=None):
+        """``graph``: the library replays the step as a HIP graph (needs a stream of its own).
+        ``grad_dtypes``: gradient precision per tensor (the workload's gradients are cast to it)."""
         self.wl = wl
         self.device = torch.device(device)
-        self.orc = make_oracle(wl, workers=workers)
+        self.grad_dtypes = grad_dtypes
+        self.orc = make_oracle(wl, workers=workers, grad_dtypes=grad_dtypes)
         params = [wl.init_param(l).to(self.device) for l in range(wl.n_tensors)]
         self.stream = torch.cuda.Stream(device=self.device) if graph else None
         torch.cuda.synchronize()
-        self.gpu = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype, stream=self.stream)
+        self.gpu = ta.TriAccel(wl.hyper, params, grad_dtype=wl.grad_dtype if grad_dtypes is None else grad_dtypes,
+                               stream=self.stream)
         if graph:
             self.gpu.set_graph(True)
         self.scale = float(wl.hyper["loss_scale"])
@@ -59,6 +63,8 @@ class Pair:
     def inputs(self, t, probe=True):
         wl = self.wl
         grads = [wl.grad(t, l, self.scale) for l in range(wl.n_tensors)]
+        if self.grad_dtypes is not None:
+            grads = [g.to(TORCH_DTYPE[d]) for g, d in zip(grads, self.grad_dtypes)]
         if probe:
             pr = [wl.probe(t, l, self.scale) for l in range(wl.n_tensors)]
             zs, hzs = [p[0] for p in pr], [p[1] for p in pr]

@@ -13,11 +13,13 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
     return t.numpy()
 
 
-def make_oracle(wl, tensors=None, workers=1):
+def make_oracle(wl, tensors=None, workers=1, grad_dtypes=None):
+    """``grad_dtypes``: gradient precision per tensor of the workload (default: the workload's one)."""
     idx = list(range(wl.n_tensors)) if tensors is None else list(tensors)
     cfg = oracle.OracleConfig.from_hyper(wl.hyper)
     params = [to_numpy(wl.init_param(l)) for l in idx]
-    return oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx], [wl.grad_dtype] * len(idx), workers=workers)
+    return oracle.OracleTriAccel(cfg, params, [wl.init_dtype(l) for l in idx],
+                                 [wl.grad_dtype if grad_dtypes is None else grad_dtypes[l] for l in idx], workers=workers)
 
 
 def layer_record(t):

@@ -118,6 +118,30 @@ def test_every_precision_transition_in_place():
             p.close()
 
 
+def test_gradient_precision_differs_from_tensor_to_tensor():
+    # the ABI takes the gradient precision per tensor: every pairing of gradient and storage precision in one set,
+    # with the storage precisions moving as the gradient scale cycles
+    sizes = [9000, 4096 * 3 + 17, 70001, 33, 140000, 8192, 4097, 300007, 5]
+    gd = [FP32, BF16, FP16, BF16, FP16, FP32, FP16, BF16, FP32]
+    wl = custom(sizes, name="large_streaming", beta_var=0.0, tau_low=1e-4, tau_high=1e-2, tau_curv=1e30)
+    p = Pair(wl, grad_dtypes=gd)
+    for t, m in enumerate([0.1, 1.0, 10.0, 1.0, 0.1, 10.0], start=1):
+        g, z, hz = p.inputs(t)
+        p.step([x * (m * 3.0) for x in g], z, hz)
+    assert {c for row in p.code_hist for c in row} == {FP16, BF16, FP32}
+    p.close()
+    # the same mix with the squared gradient as curvature sample (the EMA kernel then reads the gradients too)
+    wl = custom(sizes, name="large_streaming", beta_var=0.0, tau_low=1e-4, tau_high=1e-2, tau_curv=1e30,
+                curvature_source=1)
+    p = Pair(wl, grad_dtypes=gd)
+    none = [None] * len(sizes)
+    for t, m in enumerate([0.1, 10.0, 1.0, 0.1], start=1):
+        g, _, _ = p.inputs(t, probe=False)
+        p.step([x * (m * 3.0) for x in g], none, none)
+    assert all(o.probes_seen == 4 for o in p.orc.tensors)
+    p.close()
+
+
 def test_codes_switching_every_step():
     # variance EMA disabled (beta = 0) and a gradient scale that cycles over three decades: codes move
     # between all three precisions from step to step, exercising narrowing and widening repeatedly

@@ -219,3 +219,24 @@ def test_argument_errors():
     gpu.close()
     with pytest.raises(ta.TriAccelError):
         ta.TriAccel(dict(wl.hyper, lambda_source=1), [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)])
+
+
+def test_kernel_times_of_the_last_call_need_profiling():
+    wl = get_workload("tiny_mlp")
+    gpu = ta.TriAccel(dict(wl.hyper, power_k=2), [wl.init_param(l).to(DEV) for l in range(wl.n_tensors)])
+    us = [wl.power_start(l, 2).to(DEV) for l in range(gpu.n)]
+    hus = [u * 0.5 for u in us]
+    with pytest.raises(ta.TriAccelError):
+        gpu.power_times()            # no call yet
+    gpu.power_iter(us, hus, 2)
+    with pytest.raises(ta.TriAccelError):
+        gpu.power_times()            # the call was not timed
+    gpu.set_profiling(True)
+    gpu.power_iter(us, hus, 2)
+    times = gpu.power_times()
+    assert len(times) == 3 and all(t > 0 for t in times)
+    gpu.set_profiling(False)
+    gpu.power_iter(us, hus, 2)
+    with pytest.raises(ta.TriAccelError):
+        gpu.power_times()            # times of an earlier call are not handed out for this one
+    gpu.close()
